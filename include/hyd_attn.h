@@ -1,0 +1,145 @@
+/*
+ * hyd_attn.h - C ABI of the MI355X (gfx950) packed variable-length causal self-attention library.
+ *
+ * The operation is the per-replica hot path of Hydraulis (arXiv 2412.07894): several sequences
+ * are concatenated ("packed") into one buffer of T tokens and attention is applied to each
+ * sequence on its own, so the mask is block diagonal (and causal inside each block) and the cost
+ * is the sum of S_i^2 over the packed sequences instead of (sum S_i)^2 (paper Sec. 2.1, packing
+ * paragraph; Sec. 6.1 "Solving for one V": the latency of a packed buffer is the sum over its
+ * sequences).  One forward plus one backward over a packed buffer is the unit of work that the
+ * paper's latency model T(l,P) prices (Sec. 6.1; App. C.2: the quadratic term is attention).
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or keeps them, never synchronises the device and enqueues work only on `hip_stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream).  Results are valid once the
+ *     stream has executed the work enqueued by the call; `workspace` must stay alive until then.
+ *   - Layouts are contiguous, token major: Q, O, dO, dQ are [T][Hq][d]; K, V, dK, dV are
+ *     [T][Hkv][d]; LSE is float [Hq][T] (natural log).  dtype HYD_BF16: 2-byte bfloat16 elements,
+ *     head_dim 128; dtype HYD_FP32: 4-byte float elements, head_dim 64 or 128.  Outputs have the
+ *     dtype of the inputs and are fully overwritten.
+ *   - cu_seqlens is int32[num_seqs+1] ON THE DEVICE: cu[0] = 0, cu[num_seqs] = T, non-decreasing;
+ *     sequence s owns packed rows [cu[s], cu[s+1]).  Empty sequences are legal.  Every token
+ *     belongs to exactly one sequence.  `cu_seqlens_host` is an optional HOST copy of the same
+ *     array (may be NULL); when given it is validated before anything is enqueued.
+ *   - Query head h reads KV head h / (Hq/Hkv) (grouped-query attention with contiguous groups).
+ *   - Masking is always causal in LOCAL positions: key j of a sequence is visible to query i of
+ *     the same sequence iff j <= i.  No dropout, bias, window or positional encoding.
+ *   - Errors are return codes.  All argument validation happens before the first HIP call, so
+ *     every HYD_ERR_* below except HYD_ERR_ARCH and HYD_ERR_LAUNCH can be provoked on a host
+ *     without a GPU.  On error nothing has been enqueued.
+ *   - Calls are re-entrant as long as concurrent calls use distinct workspaces.
+ */
+#ifndef HYD_ATTN_H
+#define HYD_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HYD_OK = 0,
+    HYD_ERR_NULL = 1,       /* a required pointer is NULL */
+    HYD_ERR_SHAPE = 2,      /* negative sizes, max_seqlen smaller than the longest sequence */
+    HYD_ERR_DTYPE = 3,      /* dtype is neither HYD_BF16 nor HYD_FP32 */
+    HYD_ERR_HEADS = 4,      /* hq <= 0, hkv <= 0 or hq % hkv != 0 */
+    HYD_ERR_HEADDIM = 5,    /* head_dim not supported for this dtype */
+    HYD_ERR_SEQLENS = 6,    /* host cu_seqlens does not start at 0, end at T or is decreasing */
+    HYD_ERR_WORKSPACE = 7,  /* workspace NULL, misaligned (256 B) or smaller than required */
+    HYD_ERR_ARCH = 8,       /* the current device is not gfx950 */
+    HYD_ERR_LAUNCH = 9      /* a HIP launch or query failed */
+} hyd_status;
+
+typedef enum { HYD_BF16 = 0, HYD_FP32 = 1 } hyd_dtype;
+
+/* Human-readable name of a status code (static storage; never NULL). */
+const char* hyd_status_string(hyd_status st);
+
+/*
+ * Bytes of device workspace that hyd_varlen_attn_fwd (is_bwd = 0) or hyd_varlen_attn_bwd
+ * (is_bwd = 1) needs for these sizes.  The workspace holds the work-item schedule (the list of
+ * (sequence, tile) items ordered by decreasing cost, and the queue cursors of the persistent
+ * workgroups) and, for the backward, the float vector D[Hq][T] = rowsum(dO * O).  Returns 0 for
+ * invalid arguments.  Pure host arithmetic: no HIP call.
+ */
+size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, int hkv,
+                                       int head_dim, hyd_dtype dt, int is_bwd);
+
+/*
+ * Forward (paper Sec. 2.1: block-diagonal "varlen" attention; causal because the models are
+ * decoder-only, Sec. 8.1).  For every sequence s, query head h, local row i:
+ *     s_ij = softmax_scale * <Q_i, K_j>, j <= i;   P_i. = softmax_j(s_i.);
+ *     O_i = sum_j P_ij V_j;                        LSE_i = ln sum_j exp(s_ij).
+ *
+ *   q, k, v          device, inputs (layouts above)
+ *   cu_seqlens       device int32[num_seqs+1]
+ *   cu_seqlens_host  host copy or NULL
+ *   total_tokens     T >= 0;  max_seqlen: an upper bound on the longest sequence (1..T)
+ *   o, lse           device, outputs; rows of o / entries of lse are written for every token
+ *   workspace        device, >= hyd_varlen_attn_workspace_bytes(..., 0) bytes, 256-byte aligned;
+ *                    contents need not be initialised and are clobbered
+ * T == 0 or num_seqs == 0 is a no-op returning HYD_OK.
+ */
+hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v,
+                               const int32_t* cu_seqlens, int num_seqs,
+                               const int32_t* cu_seqlens_host,
+                               int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                               float softmax_scale, hyd_dtype dt,
+                               void* o, float* lse,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of the above for an upstream gradient dO of O (LSE carries no gradient).  One forward
+ * and one backward are the paper's unit "a single forward and backward propagation" (Sec. 6.1).
+ *     dP_ij = <dO_i, V_j>;  D_i = <dO_i, O_i>;  dS_ij = P_ij (dP_ij - D_i),  P_ij = exp(s_ij - LSE_i)
+ *     dQ_i = scale * sum_{j<=i} dS_ij K_j
+ *     dK_j = scale * sum_{h in group} sum_{i>=j} dS_ij Q_i
+ *     dV_j =         sum_{h in group} sum_{i>=j} P_ij dO_i
+ *
+ *   q, k, v, o, lse  device, the forward's inputs and outputs (o and lse as the forward wrote them)
+ *   d_o              device, [T][Hq][d], same dtype
+ *   dq, dk, dv       device, outputs, fully overwritten (no atomics: bitwise reproducible)
+ *   workspace        device, >= hyd_varlen_attn_workspace_bytes(..., 1) bytes, 256-byte aligned
+ * Three kernels are enqueued after the schedule prelude: D = rowsum(dO*O); dK/dV (one work item
+ * per (sequence, key tile, KV head), looping over the group's query heads); dQ (one work item
+ * per (sequence, query tile, query head)).
+ */
+hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o,
+                               const float* lse, const void* d_o,
+                               const int32_t* cu_seqlens, int num_seqs,
+                               const int32_t* cu_seqlens_host,
+                               int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                               float softmax_scale, hyd_dtype dt,
+                               void* dq, void* dk, void* dv,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Timing hook for benchmarks: the names and HIP-event durations (milliseconds) of the kernels
+ * the most recent fwd / bwd call on this host thread enqueued.  When enabled (on != 0) each
+ * later call brackets every kernel with events on the caller's stream; hyd_kernel_times then
+ * synchronises those events and fills up to `cap` entries of names[] (static strings) and ms[],
+ * returning the number of kernels recorded (0 when timing is off).  Off by default; when off the
+ * entry points enqueue nothing but their kernels.
+ */
+void hyd_enable_kernel_timing(int on);
+int  hyd_kernel_times(const char** names, float* ms, int cap);
+
+/*
+ * Per-workgroup busy-time instrumentation of the persistent kernels.  With a non-NULL device
+ * buffer of `capacity_records` records registered here, every persistent workgroup of the later
+ * fwd / bwd calls on this host thread writes one record of 4 x uint64:
+ *     { kernel id (0 fwd, 1 dK/dV, 2 dQ) << 32 | physical CU key (XCC id, SE id, CU id),
+ *       start clock, end clock, number of work items processed }
+ * at index (kernel id * grid + workgroup).  Pass NULL to switch it off.  The clock is the
+ * constant-rate wall clock (100 MHz).  For measurement builds only: adds two clock reads and one
+ * 32-byte store per workgroup.
+ */
+void hyd_set_wg_trace(void* device_records, int capacity_records);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYD_ATTN_H */

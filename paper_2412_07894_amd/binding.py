@@ -1,0 +1,159 @@
+"""Thin Python front end of the C-ABI library (include/hyd_attn.h): argument marshalling only.
+PyTorch supplies device memory and the current HIP stream; every step of the computation runs in
+the library's HIP kernels.  There is no fallback: if the library is missing or a call fails, an
+exception is raised."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhyd_attn.so")
+HYD_BF16, HYD_FP32 = 0, 1
+_lib = None
+
+EXPORTS = (
+    "hyd_status_string", "hyd_varlen_attn_workspace_bytes", "hyd_varlen_attn_fwd",
+    "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
+)
+
+
+class HydError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"hyd_attn error {code}: {msg}")
+        self.code = code
+
+
+def load():
+    """Load libhyd_attn.so (built by paper_2412_07894_amd/build.py; never built implicitly here)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python paper_2412_07894_amd/build.py` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.hyd_status_string.restype = ctypes.c_char_p
+    lib.hyd_status_string.argtypes = [i]
+    lib.hyd_varlen_attn_workspace_bytes.restype = sz
+    lib.hyd_varlen_attn_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.hyd_varlen_attn_fwd.restype = i
+    lib.hyd_varlen_attn_fwd.argtypes = [vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i, vp, vp, vp, sz, vp]
+    lib.hyd_varlen_attn_bwd.restype = i
+    lib.hyd_varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i,
+                                        vp, vp, vp, vp, sz, vp]
+    lib.hyd_enable_kernel_timing.restype = None
+    lib.hyd_enable_kernel_timing.argtypes = [i]
+    lib.hyd_kernel_times.restype = i
+    lib.hyd_kernel_times.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), i]
+    lib.hyd_set_wg_trace.restype = None
+    lib.hyd_set_wg_trace.argtypes = [vp, i]
+    _lib = lib
+    return lib
+
+
+def status_string(code):
+    return load().hyd_status_string(int(code)).decode()
+
+
+def _check(code):
+    if code != 0:
+        raise HydError(code, status_string(code))
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return HYD_BF16
+    if t.dtype == torch.float32:
+        return HYD_FP32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def workspace_bytes(total_tokens, num_seqs, hq, hkv, head_dim, dtype_code, is_bwd):
+    return int(load().hyd_varlen_attn_workspace_bytes(total_tokens, num_seqs, hq, hkv, head_dim,
+                                                      dtype_code, int(is_bwd)))
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _host_ptr(cu_host):
+    if cu_host is None:
+        return None, None
+    keep = (ctypes.c_int32 * len(cu_host))(*[int(x) for x in cu_host])
+    return keep, ctypes.cast(keep, ctypes.c_void_p)
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def varlen_attn_fwd(q, k, v, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_host=None,
+                    workspace=None, stream=None, out=None, lse=None):
+    """q[T,Hq,d], k,v[T,Hkv,d] contiguous device tensors (bf16 or fp32); cu_seqlens int32 device
+    tensor [num_seqs+1].  Returns (o[T,Hq,d], lse[Hq,T] fp32)."""
+    lib = load()
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
+    dt = _dtype_code(q)
+    nseq = cu_seqlens.numel() - 1
+    o = torch.empty_like(q) if out is None else out
+    lse = torch.empty((hq, T), dtype=torch.float32, device=q.device) if lse is None else lse
+    need = workspace_bytes(T, nseq, hq, hkv, d, dt, False)
+    ws = _workspace(need, q.device) if workspace is None else workspace
+    keep, hp = _host_ptr(cu_seqlens_host)
+    _check(lib.hyd_varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(), nseq,
+                                   hp, T, int(max_seqlen), hq, hkv, d, float(softmax_scale), dt,
+                                   o.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
+                                   _stream_ptr(stream)))
+    return o, lse
+
+
+def varlen_attn_bwd(q, k, v, o, lse, d_o, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_host=None,
+                    workspace=None, stream=None, dq=None, dk=None, dv=None):
+    """Returns (dq, dk, dv) with the shapes and dtype of q, k, v."""
+    lib = load()
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    for t in (q, k, v, o, d_o, lse):
+        assert t.is_contiguous()
+    dt = _dtype_code(q)
+    nseq = cu_seqlens.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = workspace_bytes(T, nseq, hq, hkv, d, dt, True)
+    ws = _workspace(need, q.device) if workspace is None else workspace
+    keep, hp = _host_ptr(cu_seqlens_host)
+    _check(lib.hyd_varlen_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                   d_o.data_ptr(), cu_seqlens.data_ptr(), nseq, hp, T, int(max_seqlen),
+                                   hq, hkv, d, float(softmax_scale), dt, dq.data_ptr(), dk.data_ptr(),
+                                   dv.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def enable_kernel_timing(on):
+    load().hyd_enable_kernel_timing(int(bool(on)))
+
+
+def kernel_times(cap=16):
+    """[(kernel name, milliseconds)] of the most recent fwd or bwd call (timing must be enabled)."""
+    names = (ctypes.c_char_p * cap)()
+    ms = (ctypes.c_float * cap)()
+    n = load().hyd_kernel_times(names, ms, cap)
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+def set_wg_trace(records):
+    """records: int64 device tensor [3 * per_kernel, 4] (or None to switch the trace off)."""
+    if records is None:
+        load().hyd_set_wg_trace(None, 0)
+    else:
+        assert records.dtype == torch.int64 and records.is_contiguous() and records.shape[1] == 4
+        load().hyd_set_wg_trace(records.data_ptr(), records.shape[0])

@@ -1,0 +1,370 @@
+// Host side of the C ABI declared in include/hyd_attn.h: argument validation (before any HIP
+// call), workspace layout, launch configuration and the benchmark hooks.
+#include "../../include/hyd_attn.h"
+
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <vector>
+
+#include "hyd_bwd_bf16.h"
+#include "hyd_fp32.h"
+#include "hyd_fwd_bf16.h"
+
+namespace {
+
+using namespace hyd;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WsLayout {
+    size_t hdr, hist, cnt_ge, offs, fill, items, dvec, total;
+    int n_lev, max_items;
+};
+
+WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
+    WsLayout w;
+    w.n_lev = (T + tile - 1) / tile;
+    if (w.n_lev < 1) w.n_lev = 1;
+    w.max_items = T / tile + nseq + 1;
+    const size_t lev_bytes = align_up(sizeof(int) * (size_t)(w.n_lev + 2));
+    size_t at = 0;
+    w.hdr = at;    at += align_up(sizeof(int) * kHdrInts);
+    w.hist = at;   at += lev_bytes;
+    w.cnt_ge = at; at += lev_bytes;
+    w.offs = at;   at += lev_bytes;
+    w.fill = at;   at += lev_bytes;
+    w.items = at;  at += align_up(sizeof(int) * 2 * (size_t)w.max_items);
+    w.dvec = at;
+    if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
+    w.total = at;
+    return w;
+}
+
+int tile_of(hyd_dtype dt) { return dt == HYD_BF16 ? kFwdBM : kF32Tile; }
+
+bool head_dim_ok(hyd_dtype dt, int d) { return dt == HYD_BF16 ? d == 128 : (d == 64 || d == 128); }
+
+// Spread of (item, head) pairs over the 8 queues: whole KV groups per queue when the KV heads
+// divide over the queues, else single heads, else items striped with all heads in every queue.
+HeadMap head_map_q(int hq, int hkv) {
+    HeadMap hm;
+    hm.heads = hq;
+    if (hkv % kQueues == 0) { hm.striped = 0; hm.hpq = hq / kQueues; hm.group = hq / hkv; }
+    else if (hq % kQueues == 0) { hm.striped = 0; hm.hpq = hq / kQueues; hm.group = 1; }
+    else { hm.striped = 1; hm.hpq = hq; hm.group = 1; }
+    return hm;
+}
+HeadMap head_map_kv(int hkv) {
+    HeadMap hm;
+    hm.heads = hkv;
+    if (hkv % kQueues == 0) { hm.striped = 0; hm.hpq = hkv / kQueues; hm.group = 1; }
+    else { hm.striped = 1; hm.hpq = hkv; hm.group = 1; }
+    return hm;
+}
+
+hyd_status validate_common(const int32_t* cu, int num_seqs, const int32_t* cu_host, int T,
+                           int max_seqlen, int hq, int hkv, int head_dim, hyd_dtype dt,
+                           const void* ws, size_t ws_bytes, bool bwd) {
+    if (dt != HYD_BF16 && dt != HYD_FP32) return HYD_ERR_DTYPE;
+    if (T < 0 || num_seqs < 0 || max_seqlen < 0) return HYD_ERR_SHAPE;
+    if (num_seqs == 0 && T != 0) return HYD_ERR_SHAPE;
+    if (hq <= 0 || hkv <= 0 || hq % hkv != 0) return HYD_ERR_HEADS;
+    if (!head_dim_ok(dt, head_dim)) return HYD_ERR_HEADDIM;
+    if (T == 0 || num_seqs == 0) return HYD_OK;
+    if (!cu) return HYD_ERR_NULL;
+    if (max_seqlen > T || max_seqlen < 1) return HYD_ERR_SHAPE;
+    if (cu_host) {
+        if (cu_host[0] != 0 || cu_host[num_seqs] != T) return HYD_ERR_SEQLENS;
+        int longest = 0;
+        for (int s = 0; s < num_seqs; ++s) {
+            const int L = cu_host[s + 1] - cu_host[s];
+            if (L < 0) return HYD_ERR_SEQLENS;
+            if (L > longest) longest = L;
+        }
+        if (longest > max_seqlen) return HYD_ERR_SHAPE;
+    }
+    const size_t need = hyd_varlen_attn_workspace_bytes(T, num_seqs, hq, hkv, head_dim, dt, bwd ? 1 : 0);
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return HYD_ERR_WORKSPACE;
+    return HYD_OK;
+}
+
+// ---- per-device state -------------------------------------------------------------------------
+struct DeviceInfo {
+    bool ready = false, ok = false;
+    int cus = 0;
+    int occ_fwd = 1, occ_dq = 1, occ_kv = 1;
+};
+DeviceInfo g_dev[64];
+
+template <typename K>
+bool prep_kernel(K kernel, int threads, int lds, int* occ) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return false;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess) return false;
+    if (occ) *occ = n < 1 ? 1 : n;
+    return true;
+}
+
+hyd_status device_info(DeviceInfo** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return HYD_ERR_LAUNCH;
+    if (dev < 0 || dev >= 64) return HYD_ERR_LAUNCH;
+    DeviceInfo& d = g_dev[dev];
+    if (!d.ready) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return HYD_ERR_LAUNCH;
+        d.ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        d.cus = prop.multiProcessorCount;
+        if (d.ok) {
+            if (!prep_kernel(hyd_fwd_bf16_kernel, kFwdThreads, kFwdLds, &d.occ_fwd) ||
+                !prep_kernel(hyd_bwd_dq_bf16_kernel, kDqThreads, kDqLds, &d.occ_dq) ||
+                !prep_kernel(hyd_bwd_dkdv_bf16_kernel, kKvThreads, kKvLds, &d.occ_kv) ||
+                !prep_kernel(hyd_bwd_dkdv_fp32_kernel<64>, kF32Tile, f32_dkdv_lds<64>(), nullptr) ||
+                !prep_kernel(hyd_bwd_dkdv_fp32_kernel<128>, kF32Tile, f32_dkdv_lds<128>(), nullptr))
+                return HYD_ERR_LAUNCH;
+        }
+        d.ready = true;
+    }
+    if (!d.ok) return HYD_ERR_ARCH;
+    *out = &d;
+    return HYD_OK;
+}
+
+// ---- benchmark hooks --------------------------------------------------------------------------
+struct TimedKernel { const char* name; hipEvent_t e0, e1; };
+thread_local bool t_timing = false;
+thread_local std::vector<TimedKernel> t_timed;
+thread_local WgTrace t_trace = {nullptr, 0};
+
+void timed_clear() {
+    for (auto& t : t_timed) { (void)hipEventDestroy(t.e0); (void)hipEventDestroy(t.e1); }
+    t_timed.clear();
+}
+
+struct KernelTimer {       // brackets one launch with events when timing is on
+    hipStream_t st; bool on; TimedKernel tk;
+    KernelTimer(const char* name, hipStream_t s) : st(s), on(t_timing) {
+        tk.name = name;
+        if (on) {
+            on = hipEventCreate(&tk.e0) == hipSuccess && hipEventCreate(&tk.e1) == hipSuccess;
+            if (on) (void)hipEventRecord(tk.e0, st);
+        }
+    }
+    ~KernelTimer() {
+        if (on) { (void)hipEventRecord(tk.e1, st); t_timed.push_back(tk); }
+    }
+};
+
+SchedView make_view(char* ws, const WsLayout& w) {
+    SchedView sv;
+    sv.hdr = reinterpret_cast<int*>(ws + w.hdr);
+    sv.hist = reinterpret_cast<int*>(ws + w.hist);
+    sv.cnt_ge = reinterpret_cast<int*>(ws + w.cnt_ge);
+    sv.offs = reinterpret_cast<int*>(ws + w.offs);
+    sv.fill = reinterpret_cast<int*>(ws + w.fill);
+    sv.items = reinterpret_cast<int*>(ws + w.items);
+    sv.n_lev = w.n_lev;
+    sv.max_items = w.max_items;
+    return sv;
+}
+
+int persistent_grid(const DeviceInfo& d, int occ, long long work_upper_bound) {
+    long long g = (long long)d.cus * occ;
+    if (g > work_upper_bound) g = work_upper_bound;
+    return g < 1 ? 1 : (int)g;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hyd_status_string(hyd_status st) {
+    switch (st) {
+        case HYD_OK: return "HYD_OK";
+        case HYD_ERR_NULL: return "HYD_ERR_NULL: a required pointer is NULL";
+        case HYD_ERR_SHAPE: return "HYD_ERR_SHAPE: negative size or max_seqlen out of range";
+        case HYD_ERR_DTYPE: return "HYD_ERR_DTYPE: unknown dtype";
+        case HYD_ERR_HEADS: return "HYD_ERR_HEADS: hq and hkv must be positive with hq % hkv == 0";
+        case HYD_ERR_HEADDIM: return "HYD_ERR_HEADDIM: head_dim must be 128 (bf16) or 64/128 (fp32)";
+        case HYD_ERR_SEQLENS: return "HYD_ERR_SEQLENS: cu_seqlens must start at 0, end at T and not decrease";
+        case HYD_ERR_WORKSPACE: return "HYD_ERR_WORKSPACE: workspace NULL, misaligned or too small";
+        case HYD_ERR_ARCH: return "HYD_ERR_ARCH: device is not gfx950";
+        case HYD_ERR_LAUNCH: return "HYD_ERR_LAUNCH: HIP launch or query failed";
+    }
+    return "unknown hyd_status";
+}
+
+size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, int hkv, int head_dim,
+                                       hyd_dtype dt, int is_bwd) {
+    if (total_tokens < 0 || num_seqs < 0 || hq <= 0 || hkv <= 0 || hq % hkv != 0) return 0;
+    if ((dt != HYD_BF16 && dt != HYD_FP32) || !head_dim_ok(dt, head_dim)) return 0;
+    return ws_layout(total_tokens, num_seqs, tile_of(dt), hq, is_bwd != 0).total;
+}
+
+hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                               int num_seqs, const int32_t* cu_seqlens_host, int total_tokens,
+                               int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
+                               hyd_dtype dt, void* o, float* lse, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+    const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
+                                          hq, hkv, head_dim, dt, workspace, workspace_bytes, false);
+    if (vs != HYD_OK) return vs;
+    if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
+    if (!q || !k || !v || !o || !lse) return HYD_ERR_NULL;
+
+    DeviceInfo* dev = nullptr;
+    const hyd_status ds = device_info(&dev);
+    if (ds != HYD_OK) return ds;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (t_timing) timed_clear();
+
+    const int tile = tile_of(dt);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, false);
+    const SchedView sv = make_view(static_cast<char*>(workspace), w);
+    {
+        KernelTimer kt("schedule_prelude", st);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile, sv);
+    }
+    const HeadMap hm = head_map_q(hq, hkv);
+    const long long work = (long long)w.max_items * hq;
+    if (dt == HYD_BF16) {
+        FwdParams p;
+        p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
+        p.v = static_cast<const uint16_t*>(v); p.o = static_cast<uint16_t*>(o); p.lse = lse;
+        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv;
+        p.scale_log2 = softmax_scale * kLog2e;
+        p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
+        KernelTimer kt("fwd_bf16", st);
+        hipLaunchKernelGGL(hyd_fwd_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_fwd, work)),
+                           dim3(kFwdThreads), kFwdLds, st, p);
+    } else {
+        F32Params p;
+        memset(&p, 0, sizeof(p));
+        p.q = static_cast<const float*>(q); p.k = static_cast<const float*>(k);
+        p.v = static_cast<const float*>(v); p.o_out = static_cast<float*>(o); p.lse_out = lse;
+        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
+        p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
+        const int grid = persistent_grid(*dev, 8, work);
+        KernelTimer kt("fwd_fp32", st);
+        if (head_dim == 64) hipLaunchKernelGGL(hyd_fwd_fp32_kernel<64>, dim3(grid), dim3(kF32Tile), 0, st, p);
+        else hipLaunchKernelGGL(hyd_fwd_fp32_kernel<128>, dim3(grid), dim3(kF32Tile), 0, st, p);
+    }
+    return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
+}
+
+hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                               const void* d_o, const int32_t* cu_seqlens, int num_seqs,
+                               const int32_t* cu_seqlens_host, int total_tokens, int max_seqlen, int hq,
+                               int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq, void* dk,
+                               void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
+                                          hq, hkv, head_dim, dt, workspace, workspace_bytes, true);
+    if (vs != HYD_OK) return vs;
+    if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return HYD_ERR_NULL;
+
+    DeviceInfo* dev = nullptr;
+    const hyd_status ds = device_info(&dev);
+    if (ds != HYD_OK) return ds;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (t_timing) timed_clear();
+
+    const int tile = tile_of(dt);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, true);
+    char* ws = static_cast<char*>(workspace);
+    const SchedView sv = make_view(ws, w);
+    float* Dvec = reinterpret_cast<float*>(ws + w.dvec);
+    {
+        KernelTimer kt("schedule_prelude", st);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile, sv);
+    }
+    const long long n_rows = (long long)total_tokens * hq;
+    const long long work_q = (long long)w.max_items * hq, work_kv = (long long)w.max_items * hkv;
+    if (dt == HYD_BF16) {
+        {
+            KernelTimer kt("bwd_rowdot_bf16", st);
+            hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st,
+                               static_cast<const uint16_t*>(o), static_cast<const uint16_t*>(d_o), Dvec,
+                               total_tokens, hq);
+        }
+        BwdParams p;
+        p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
+        p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
+        p.lse = lse; p.D = Dvec;
+        p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
+        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv;
+        p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
+        p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
+        {
+            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            KernelTimer kt("bwd_dkdv_bf16", st);
+            hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_kv, work_kv)),
+                               dim3(kKvThreads), kKvLds, st, p);
+        }
+        {
+            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            KernelTimer kt("bwd_dq_bf16", st);
+            hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_dq, work_q)),
+                               dim3(kDqThreads), kDqLds, st, p);
+        }
+    } else {
+        F32Params p;
+        memset(&p, 0, sizeof(p));
+        p.q = static_cast<const float*>(q); p.k = static_cast<const float*>(k);
+        p.v = static_cast<const float*>(v); p.o = static_cast<const float*>(o);
+        p.d_o = static_cast<const float*>(d_o); p.lse_in = lse; p.D = Dvec;
+        p.dq = static_cast<float*>(dq); p.dk = static_cast<float*>(dk); p.dv = static_cast<float*>(dv);
+        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
+        p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
+        const unsigned rd_grid = (unsigned)((n_rows + 255) / 256);
+        const int grid_q = persistent_grid(*dev, 8, work_q), grid_kv = persistent_grid(*dev, 2, work_kv);
+        if (head_dim == 64) {
+            { KernelTimer kt("bwd_rowdot_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_rowdot_fp32_kernel<64>, dim3(rd_grid), dim3(256), 0, st, p.o, p.d_o, Dvec, total_tokens, hq); }
+            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            { KernelTimer kt("bwd_dkdv_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_dkdv_fp32_kernel<64>, dim3(grid_kv), dim3(kF32Tile), f32_dkdv_lds<64>(), st, p); }
+            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            { KernelTimer kt("bwd_dq_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_dq_fp32_kernel<64>, dim3(grid_q), dim3(kF32Tile), 0, st, p); }
+        } else {
+            { KernelTimer kt("bwd_rowdot_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_rowdot_fp32_kernel<128>, dim3(rd_grid), dim3(256), 0, st, p.o, p.d_o, Dvec, total_tokens, hq); }
+            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            { KernelTimer kt("bwd_dkdv_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_dkdv_fp32_kernel<128>, dim3(grid_kv), dim3(kF32Tile), f32_dkdv_lds<128>(), st, p); }
+            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            { KernelTimer kt("bwd_dq_fp32", st);
+              hipLaunchKernelGGL(hyd_bwd_dq_fp32_kernel<128>, dim3(grid_q), dim3(kF32Tile), 0, st, p); }
+        }
+    }
+    return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
+}
+
+void hyd_enable_kernel_timing(int on) {
+    t_timing = on != 0;
+    if (!t_timing) timed_clear();
+}
+
+int hyd_kernel_times(const char** names, float* ms, int cap) {
+    int n = 0;
+    for (auto& t : t_timed) {
+        if (n >= cap) break;
+        float dt = 0.f;
+        if (hipEventSynchronize(t.e1) != hipSuccess || hipEventElapsedTime(&dt, t.e0, t.e1) != hipSuccess) dt = -1.f;
+        names[n] = t.name;
+        ms[n] = dt;
+        ++n;
+    }
+    return n;
+}
+
+void hyd_set_wg_trace(void* device_records, int capacity_records) {
+    t_trace.rec = static_cast<unsigned long long*>(device_records);
+    t_trace.capacity = device_records ? capacity_records : 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,358 @@
+// bf16 backward kernels: D = rowsum(dO * O), dK/dV, and dQ.  No atomics: every output element has
+// exactly one producing wave with a fixed summation order, so results are bitwise reproducible.
+//
+// Fragment convention (see hyd_device.h): an MFMA operand fragment is "lane <-> one index, 8
+// register slots <-> contraction index" and can be used as the A or the B operand alike; the
+// product D[a][b] then has the A fragment's lane index as its row and B's as its column, and an
+// accumulator in turn is a fragment whose lane index is the column and whose slots are rows.
+#pragma once
+#include "hyd_sched.h"
+
+namespace hyd {
+
+// ---------------------------------------------------------------------------------------------
+// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32).  16 lanes per (token, head) row.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t* __restrict__ o,
+                                                                 const uint16_t* __restrict__ d_o,
+                                                                 float* __restrict__ D, int T, int hq) {
+    const int64_t n_rows = (int64_t)T * hq;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c = threadIdx.x & 15;
+    float acc = 0.f;
+    if (row < n_rows) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * kHeadDim + c * 8);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + row * kHeadDim + c * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
+    }
+    acc += __shfl_xor(acc, 1, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 4, 64);
+    acc += __shfl_xor(acc, 8, 64);
+    if (row < n_rows && c == 0) {
+        const int t = (int)(row / hq), h = (int)(row % hq);
+        D[(int64_t)h * T + t] = acc;
+    }
+}
+
+struct BwdParams {
+    const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
+    const float* lse; const float* D;
+    uint16_t* dq; uint16_t* dk; uint16_t* dv;
+    const int32_t* cu;
+    int T, hq, hkv;
+    float scale, scale_log2;
+    const int* hdr; int* cursors; const int* items;
+    HeadMap hm;
+    WgTrace tr;
+};
+
+constexpr float kLog2e = 1.44269504088896340736f;
+
+// Writes a transposed accumulator set acc[4] (rows = head dim, column = this lane's token) as one
+// bf16 row fragment: lane (l32, half) owns columns 32*db + 8*rq + 4*half + {0..3}.
+__device__ __forceinline__ void store_rows_bf16(uint16_t* row_ptr, const f32x16 (&acc)[4], float mul, int half) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            u32x2 w = {pack_bf16(acc[db][4 * rq] * mul, acc[db][4 * rq + 1] * mul),
+                       pack_bf16(acc[db][4 * rq + 2] * mul, acc[db][4 * rq + 3] * mul)};
+            *reinterpret_cast<u32x2*>(row_ptr + 32 * db + 8 * rq + 4 * half) = w;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ.  Work item = (sequence, 128-row query tile, query head); wave w owns rows 32w..32w+31.
+// Same orientation as the forward: S^T[key][q] = K Q^T and dP^T[key][q] = V dO^T put one query
+// row in each lane, so LSE_i and D_i are per-lane scalars; dS^T then is the B operand of
+// dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing LDS read of the same K tile.
+// ---------------------------------------------------------------------------------------------
+constexpr int kDqBM = 128, kDqBN = 64, kDqThreads = 256;
+constexpr int kDqTileBytes = kDqBN * kRowBytes;
+constexpr int kDqLds = 4 * kDqTileBytes + 64;
+
+template <bool MASK>
+__device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, int kb, const bf16x8 (&qf)[8],
+                                         const bf16x8 (&dof)[8], f32x16 (&acc)[4], float scale_log2,
+                                         float lse2, float Dq, int key0, int qrow, int lane) {
+    const int l32 = lane & 31, half = lane >> 5;
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_row_frag(Kt, 32 * kb + l32, ks, half), qf[ks], s);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_row_frag(Vt, 32 * kb + l32, ks, half), dof[ks], dp);
+    uint32_t pk[8];
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+        float t0 = __builtin_fmaf(s[r], scale_log2, -lse2);
+        float t1 = __builtin_fmaf(s[r + 1], scale_log2, -lse2);
+        if (MASK) {
+            const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key > qrow) t0 = -INFINITY;
+            if (key + 1 > qrow) t1 = -INFINITY;
+        }
+        const float p0 = __builtin_amdgcn_exp2f(t0), p1 = __builtin_amdgcn_exp2f(t1);
+        pk[r >> 1] = pack_bf16(p0 * (dp[r] - Dq), p1 * (dp[r + 1] - Dq));
+    }
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+        u32x4 dv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
+        const bf16x8 dsb = as_bf16x8(dv);
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            acc[db] = mfma32(lds_col_frag(Kt, 2 * kb + b2, db, lane), dsb, acc[db]);
+    }
+}
+
+__global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int* slot = reinterpret_cast<int*>(smem + 4 * kDqTileBytes);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int G = p.hq / p.hkv;
+    const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
+    unsigned long long n_done = 0;
+
+    WorkFetcher wf;
+    wf.init();
+    int seq, lev, head;
+    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, head)) {
+        ++n_done;
+        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+        const int q0 = (lev - 1) * kDqBM;
+        const int kv_end = min(L, q0 + kDqBM);
+        const int n_kt = (kv_end + kDqBN - 1) / kDqBN;
+        const int g = head / G;
+        const int wrow0 = q0 + 32 * wave;
+        const int qrow = wrow0 + l32;
+        const bool qvalid = qrow < L;
+
+        bf16x8 qf[8], dof[8];
+        float lse2 = 0.f, Dq = 0.f;
+        {
+            const int64_t off = (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+                if (qvalid) {
+                    a = *reinterpret_cast<const u32x4*>(p.q + off + 16 * ks);
+                    b = *reinterpret_cast<const u32x4*>(p.d_o + off + 16 * ks);
+                }
+                qf[ks] = as_bf16x8(a);
+                dof[ks] = as_bf16x8(b);
+            }
+            if (qvalid) {
+                lse2 = p.lse[(int64_t)head * p.T + row0 + qrow] * kLog2e;
+                Dq = p.D[(int64_t)head * p.T + row0 + qrow];
+            }
+        }
+        f32x16 acc[4];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+        TileMover<kDqBN, kDqThreads> mk, mv;
+        mk.load(p.k, kv_stride, g, row0, row0 + kv_end, tid);
+        mv.load(p.v, kv_stride, g, row0, row0 + kv_end, tid);
+        mk.store(smem, tid);
+        mv.store(smem + kDqTileBytes, tid);
+        __syncthreads();
+        for (int kt = 0; kt < n_kt; ++kt) {
+            char* Kt = smem + (kt & 1) * 2 * kDqTileBytes;
+            char* Vt = Kt + kDqTileBytes;
+            const bool more = kt + 1 < n_kt;
+            if (more) {
+                mk.load(p.k, kv_stride, g, row0 + (kt + 1) * kDqBN, row0 + kv_end, tid);
+                mv.load(p.v, kv_stride, g, row0 + (kt + 1) * kDqBN, row0 + kv_end, tid);
+            }
+            const int key0 = kt * kDqBN;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int kfirst = key0 + 32 * kb;
+                if (kfirst <= wrow0 + 31) {
+                    if (kfirst + 31 > wrow0)
+                        dq_block<true>(Kt, Vt, kb, qf, dof, acc, p.scale_log2, lse2, Dq, key0, qrow, lane);
+                    else
+                        dq_block<false>(Kt, Vt, kb, qf, dof, acc, p.scale_log2, lse2, Dq, key0, qrow, lane);
+                }
+            }
+            if (more) {
+                char* Kn = smem + ((kt + 1) & 1) * 2 * kDqTileBytes;
+                mk.store(Kn, tid);
+                mv.store(Kn + kDqTileBytes, tid);
+            }
+            __syncthreads();
+        }
+        if (qvalid)
+            store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
+    }
+    trace_write(p.tr, 2, t_start, n_done);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK/dV.  Work item = (sequence, 128-key tile, KV head); wave w owns keys 32w..32w+31 and keeps
+// their K and V rows in registers as B fragments.  Query tiles of 64 rows (Q, dO, LSE, D) stream
+// through LDS, for every query head of the KV group in turn, accumulating into the same dK/dV
+// registers.  S[i][j] = Q K^T and dP[i][j] = dO V^T put one KEY in each lane (column) and query
+// rows in the accumulator slots, so P and dS are directly the B fragments (contraction index =
+// query row) of dV^T[d][j] = dO^T P and dK^T[d][j] = Q^T dS, whose A fragments come from the
+// transposing LDS read of the same dO and Q tiles.
+// ---------------------------------------------------------------------------------------------
+constexpr int kKvBN = 128, kKvBM = 64, kKvThreads = 256;
+constexpr int kKvTileBytes = kKvBM * kRowBytes;                       // 16 KB
+constexpr int kKvStage = 2 * kKvTileBytes + 2 * kKvBM * 4;            // Q, dO, lse2, D
+constexpr int kKvLds = 2 * kKvStage + 64;
+
+template <bool MASK>
+__device__ __forceinline__ void dkdv_block(const char* Qt, const char* dOt, const float* lse2_t,
+                                           const float* D_t, int ib, const bf16x8 (&kf)[8],
+                                           const bf16x8 (&vf)[8], f32x16 (&acc_dk)[4], f32x16 (&acc_dv)[4],
+                                           float scale_log2, int qt0, int key, int lane) {
+    const int l32 = lane & 31, half = lane >> 5;
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_row_frag(Qt, 32 * ib + l32, ks, half), kf[ks], s);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_row_frag(dOt, 32 * ib + l32, ks, half), vf[ks], dp);
+    uint32_t pp[8], pd[8];
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        const int i0 = 32 * ib + 8 * rq + 4 * half;           // first of 4 consecutive query rows
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2_t + i0);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(D_t + i0);
+        float pv[4], dsv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float t = __builtin_fmaf(s[4 * rq + e], scale_log2, -l4[e]);
+            if (MASK) { if (key > qt0 + i0 + e) t = -INFINITY; }
+            pv[e] = __builtin_amdgcn_exp2f(t);
+            dsv[e] = pv[e] * (dp[4 * rq + e] - d4[e]);
+        }
+        pp[2 * rq] = pack_bf16(pv[0], pv[1]);  pp[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
+        pd[2 * rq] = pack_bf16(dsv[0], dsv[1]); pd[2 * rq + 1] = pack_bf16(dsv[2], dsv[3]);
+    }
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+        u32x4 a = {pp[4 * b2], pp[4 * b2 + 1], pp[4 * b2 + 2], pp[4 * b2 + 3]};
+        u32x4 b = {pd[4 * b2], pd[4 * b2 + 1], pd[4 * b2 + 2], pd[4 * b2 + 3]};
+        const bf16x8 pfr = as_bf16x8(a), dsfr = as_bf16x8(b);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            acc_dv[db] = mfma32(lds_col_frag(dOt, 2 * ib + b2, db, lane), pfr, acc_dv[db]);
+            acc_dk[db] = mfma32(lds_col_frag(Qt, 2 * ib + b2, db, lane), dsfr, acc_dk[db]);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int* slot = reinterpret_cast<int*>(smem + 2 * kKvStage);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int G = p.hq / p.hkv;
+    const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
+    unsigned long long n_done = 0;
+
+    WorkFetcher wf;
+    wf.init();
+    int seq, lev, g;
+    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, g)) {
+        ++n_done;
+        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+        const int n_tiles = (L + kKvBN - 1) / kKvBN;
+        const int j0 = (n_tiles - lev) * kKvBN;               // first key of the item
+        const int wkey0 = j0 + 32 * wave;                     // first key of this wave
+        const int key = wkey0 + l32;
+        const bool kvalid = key < L;
+        const int qt_first = j0 / kKvBM;                      // first query tile that sees key j0
+        const int n_qt = (L + kKvBM - 1) / kKvBM - qt_first;
+        const int n_iter = n_qt * G;
+
+        bf16x8 kf[8], vf[8];
+        {
+            const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+                if (kvalid) {
+                    a = *reinterpret_cast<const u32x4*>(p.k + off + 16 * ks);
+                    b = *reinterpret_cast<const u32x4*>(p.v + off + 16 * ks);
+                }
+                kf[ks] = as_bf16x8(a);
+                vf[ks] = as_bf16x8(b);
+            }
+        }
+        f32x16 acc_dk[4], acc_dv[4];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc_dk[db][r] = 0.f; acc_dv[db][r] = 0.f; }
+
+        TileMover<kKvBM, kKvThreads> mq, mdo;
+        float stat = 0.f;                                     // threads 0..63: lse2, 64..127: D
+        auto stage_load = [&](int it) {
+            const int h = g * G + it / n_qt;
+            const int qt0 = (qt_first + it % n_qt) * kKvBM;
+            mq.load(p.q, q_stride, h, row0 + qt0, row0 + L, tid);
+            mdo.load(p.d_o, q_stride, h, row0 + qt0, row0 + L, tid);
+            if (tid < 2 * kKvBM) {
+                const int i = qt0 + (tid & (kKvBM - 1));
+                const bool is_lse = tid < kKvBM;
+                stat = is_lse ? INFINITY : 0.f;               // rows past the end: P = exp2(-inf) = 0
+                if (i < L) {
+                    const int64_t at = (int64_t)h * p.T + row0 + i;
+                    stat = is_lse ? p.lse[at] * kLog2e : p.D[at];
+                }
+            }
+        };
+        auto stage_store = [&](int buf) {
+            char* base = smem + buf * kKvStage;
+            mq.store(base, tid);
+            mdo.store(base + kKvTileBytes, tid);
+            if (tid < 2 * kKvBM) reinterpret_cast<float*>(base + 2 * kKvTileBytes)[tid] = stat;
+        };
+        stage_load(0);
+        stage_store(0);
+        __syncthreads();
+        for (int it = 0; it < n_iter; ++it) {
+            const char* base = smem + (it & 1) * kKvStage;
+            const char* Qt = base;
+            const char* dOt = base + kKvTileBytes;
+            const float* lse2_t = reinterpret_cast<const float*>(base + 2 * kKvTileBytes);
+            const float* D_t = lse2_t + kKvBM;
+            const bool more = it + 1 < n_iter;
+            if (more) stage_load(it + 1);
+            const int qt0 = (qt_first + it % n_qt) * kKvBM;
+#pragma unroll
+            for (int ib = 0; ib < 2; ++ib) {
+                const int ifirst = qt0 + 32 * ib;             // first query row of the block
+                if (ifirst + 31 >= wkey0) {                   // some row sees some key of the wave
+                    if (ifirst < wkey0 + 31)
+                        dkdv_block<true>(Qt, dOt, lse2_t, D_t, ib, kf, vf, acc_dk, acc_dv, p.scale_log2, qt0, key, lane);
+                    else
+                        dkdv_block<false>(Qt, dOt, lse2_t, D_t, ib, kf, vf, acc_dk, acc_dv, p.scale_log2, qt0, key, lane);
+                }
+            }
+            if (more) stage_store((it + 1) & 1);
+            __syncthreads();
+        }
+        if (kvalid) {
+            const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim;
+            store_rows_bf16(p.dk + off, acc_dk, p.scale, half);
+            store_rows_bf16(p.dv + off, acc_dv, 1.f, half);
+        }
+    }
+    trace_write(p.tr, 1, t_start, n_done);
+}
+
+}  // namespace hyd

@@ -1,0 +1,183 @@
+// Work-item schedule of the persistent attention kernels.
+//
+// A work item is (sequence s, level c) with 1 <= c <= n_s = ceil(L_s / tile).  The forward and
+// the dQ kernel read it as query tile c-1, whose causal span is c key tiles; the dK/dV kernel
+// reads it as key tile n_s - c, which c query tiles attend to.  Either way the item's cost is
+// proportional to c: the quadratic attention cost of a sequence (paper Sec. 2.1: cost is the sum
+// of S_i^2; App. C.2: the quadratic term of T(l,P)) split into a ramp 1..n_s.  The prelude kernel
+// writes the items in order of decreasing c.  Persistent workgroups then take items from the
+// front of that list through atomic cursors, so the next-longest item always goes to the first
+// workgroup that becomes free: longest-processing-time-first list scheduling.
+//
+// Heads multiply the items.  To keep the workgroups of one XCD (which share an L2) on the same
+// K/V heads, the (item, head) space is split into 8 queues, one per XCD; a workgroup drains the
+// queue of the XCD it runs on and then steals from the others, so every launch ends with all
+// queues empty and no workgroup waits on another.
+#pragma once
+#include "hyd_device.h"
+
+namespace hyd {
+
+constexpr int kQueues = 8;
+constexpr int kHdrInts = 64;
+// header (ints): [0] n_items, [8 + 8*k + x] cursor of queue x of kernel k (k = 0 fwd, 1 dK/dV, 2 dQ)
+constexpr int kHdrCursor = 8;
+
+struct SchedView {            // device pointers into the workspace (all int32)
+    int* hdr;                 // kHdrInts
+    int* hist;                // n_lev + 2 : number of sequences with exactly n tiles
+    int* cnt_ge;              // n_lev + 2 : number of sequences with >= c tiles
+    int* offs;                // n_lev + 2 : first list position of level c
+    int* fill;                // n_lev + 2 : scratch counters
+    int* items;               // 2 * max_items : (s, c) pairs, decreasing c
+    int n_lev;                // upper bound on tiles per sequence
+    int max_items;
+};
+
+struct HeadMap {              // how (item, head) pairs are spread over the queues
+    int striped;              // 0: heads partitioned over the queues; 1: items striped
+    int heads;                // heads per item (Hq for fwd/dQ, Hkv for dK/dV)
+    int hpq;                  // partitioned: heads per queue
+    int group;                // partitioned: consecutive work indices share group-size heads
+};
+
+// In-place inclusive scan of v[0..n) by one workgroup of NT threads (n arbitrary).
+template <int NT>
+__device__ void block_inclusive_scan(int* v, int n, int* lds /*NT ints*/) {
+    const int tid = threadIdx.x;
+    const int chunk = (n + NT - 1) / NT;
+    const int lo = tid * chunk, hi = min(n, lo + chunk);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += v[i];
+    lds[tid] = sum;
+    __syncthreads();
+    for (int d = 1; d < NT; d <<= 1) {
+        int add = (tid >= d) ? lds[tid - d] : 0;
+        __syncthreads();
+        lds[tid] += add;
+        __syncthreads();
+    }
+    int run = lds[tid] - sum;
+    for (int i = lo; i < hi; ++i) { run += v[i]; v[i] = run; }
+    __syncthreads();
+}
+
+// One workgroup of 1024 threads.  Builds the item list for tile size `tile` and clears the
+// cursors.  Order among items of equal cost is unspecified (it never changes a result: every
+// output element has exactly one producer).
+__global__ void __launch_bounds__(1024) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq,
+                                                             int tile, SchedView sv) {
+    __shared__ int lds[1024];
+    const int tid = threadIdx.x;
+    const int nl = sv.n_lev;
+    for (int i = tid; i < nl + 2; i += 1024) { sv.hist[i] = 0; sv.fill[i] = 0; }
+    for (int i = tid; i < kHdrInts; i += 1024) sv.hdr[i] = 0;
+    __syncthreads();
+    for (int s = tid; s < nseq; s += 1024) {
+        const int L = cu[s + 1] - cu[s];
+        const int n = min((L + tile - 1) / tile, nl);
+        if (n > 0) atomicAdd(&sv.hist[n], 1);
+    }
+    __syncthreads();
+    // cnt_ge[c] = sum_{n >= c} hist[n]; scan in reversed index order r = nl - c (c = nl .. 1)
+    for (int r = tid; r < nl; r += 1024) sv.cnt_ge[r] = sv.hist[nl - r];
+    __syncthreads();
+    block_inclusive_scan<1024>(sv.cnt_ge, nl, lds);
+    // offs (reversed order) = exclusive scan of cnt_ge (reversed order)
+    for (int r = tid; r < nl; r += 1024) sv.offs[r] = sv.cnt_ge[r];
+    __syncthreads();
+    block_inclusive_scan<1024>(sv.offs, nl, lds);
+    if (tid == 0) sv.hdr[0] = (nl > 0) ? sv.offs[nl - 1] : 0;       // total number of items
+    // A sequence with n tiles gets rank = (#sequences with more tiles) + arrival order.
+    // Level c (reversed index r = nl - c) starts at offs[r] - cnt_ge[r] and holds the
+    // sequences of rank < cnt_ge[r].
+    for (int s = tid; s < nseq; s += 1024) {
+        const int L = cu[s + 1] - cu[s];
+        const int n = min((L + tile - 1) / tile, nl);
+        if (n == 0) continue;
+        const int more = (n < nl) ? sv.cnt_ge[nl - (n + 1)] : 0;
+        const int rank = more + atomicAdd(&sv.fill[n], 1);
+        for (int c = 1; c <= n; ++c) {
+            const int r = nl - c;
+            const int pos = sv.offs[r] - sv.cnt_ge[r] + rank;
+            if (pos < sv.max_items) { sv.items[2 * pos] = s; sv.items[2 * pos + 1] = c; }
+        }
+    }
+}
+
+// Number of work indices of queue x.
+__device__ __forceinline__ int queue_size(const HeadMap& hm, int n_items, int x) {
+    if (hm.striped) return ((n_items - x + kQueues - 1) / kQueues) * hm.heads;
+    return n_items * hm.hpq;
+}
+
+// Work index w of queue x -> (item index, head).
+__device__ __forceinline__ void decode_work(const HeadMap& hm, int x, int w, int& item, int& head) {
+    if (hm.striped) {
+        item = x + kQueues * (w / hm.heads);
+        head = w % hm.heads;
+    } else {
+        item = w / hm.hpq;
+        const int e = w % hm.hpq;
+        head = (x + kQueues * (e / hm.group)) * hm.group + e % hm.group;
+    }
+}
+
+// Persistent-workgroup work fetch.  Thread 0 takes the next index of the current queue, moving on
+// to the next queue when one is exhausted; the result is broadcast through LDS.  Returns false
+// when all queues are empty (every workgroup reaches this: the cursors only grow).
+struct WorkFetcher {
+    int queue;      // current queue
+    int tried;      // queues found empty so far
+    __device__ __forceinline__ void init() {
+        queue = (__smid() >> 6) & (kQueues - 1);     // XCC id of this workgroup
+        tried = 0;
+    }
+    // `slot`: 4 ints of LDS.  All threads must call this; contains two barriers.
+    __device__ __forceinline__ bool next(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
+                                         const int* __restrict__ items, int* slot, int& seq, int& lev,
+                                         int& head) {
+        __syncthreads();        // previous item's readers of `slot` are done
+        if (threadIdx.x == 0) {
+            const int n_items = hdr[0];
+            int item = -1, hd = 0;
+            while (tried < kQueues) {
+                const int size = queue_size(hm, n_items, queue);
+                int w = size > 0 ? atomicAdd(&cursors[queue], 1) : size;
+                if (w < size) { decode_work(hm, queue, w, item, hd); break; }
+                queue = (queue + 1) & (kQueues - 1);
+                ++tried;
+            }
+            slot[0] = item;
+            slot[1] = hd;
+            if (item >= 0) { slot[2] = items[2 * item]; slot[3] = items[2 * item + 1]; }
+        }
+        __syncthreads();
+        const int item = slot[0];
+        if (item < 0) return false;
+        head = slot[1]; seq = slot[2]; lev = slot[3];
+        return true;
+    }
+};
+
+// Optional per-workgroup trace record: {kernel id << 32 | CU key, start, end, items}.
+struct WgTrace {
+    unsigned long long* rec;      // nullptr: off
+    int capacity;
+};
+__device__ __forceinline__ void trace_write(const WgTrace& tr, int kernel_id, unsigned long long t0,
+                                            unsigned long long n_items_done) {
+    if (tr.rec && threadIdx.x == 0) {
+        const int per_kernel = tr.capacity / 3;
+        const int idx = kernel_id * per_kernel + blockIdx.x;
+        if ((int)blockIdx.x < per_kernel) {
+            unsigned long long* r = tr.rec + 4 * (size_t)idx;
+            r[0] = ((unsigned long long)kernel_id << 32) | (unsigned long long)__smid();
+            r[1] = t0;
+            r[2] = wall_clock64();
+            r[3] = n_items_done;
+        }
+    }
+}
+
+}  // namespace hyd
