@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: packed varlen causal attention, forward + backward, on one MI355X.
+
+One "step" is one forward call plus one backward call (schedule prelude, forward kernel,
+D = rowsum(dO*O), dK/dV kernel, dQ kernel) over one synthetic packed batch that is already
+resident in HBM.  The headline workload is configuration 2 of the benchmark spec (7B-like layer: one
+16384-token buffer of log-normal lengths, 32 heads, head_dim 128, bf16); `--config N` selects
+another one.  Prints ONE JSON line:
+    value        useful causal TFLOP/s = 14 * d * Hq * sum_s L_s (L_s + 1) / 2 / step time
+    roofline     the dominant kernel (dK/dV) against the bf16 dense MFMA peak, its duration
+                 measured with HIP events on the launch stream inside the timed region
+    cpu_baseline the fp64 oracle timed on this host's cores on a bounded sample of the workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
+
+
+def gpu_inputs(cfg, lengths, seed):
+    import torch
+    from paper_2412_07894_amd import workloads as wl
+    T = cfg.total_tokens
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+
+    def rnd(h):
+        return torch.randn((T, h, cfg.d), device="cuda", dtype=torch.float32, generator=g).to(dt)
+    cu = torch.from_numpy(wl.cu_seqlens(lengths)).cuda()
+    return rnd(cfg.hq), rnd(cfg.hkv), rnd(cfg.hkv), rnd(cfg.hq), cu
+
+
+def run_gpu(cid, steps, warmup):
+    import torch
+    from paper_2412_07894_amd import binding, workloads as wl
+    cfg = wl.CONFIGS[cid]
+    lengths = wl.seqlens(cid)
+    q, k, v, do, cu = gpu_inputs(cfg, lengths, seed=1000 * cid)
+    T, nseq, ml = cfg.total_tokens, len(lengths), int(max(lengths))
+    code = binding.HYD_BF16 if cfg.dtype == "bf16" else binding.HYD_FP32
+    ws_f = torch.empty(binding.workspace_bytes(T, nseq, cfg.hq, cfg.hkv, cfg.d, code, 0), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.workspace_bytes(T, nseq, cfg.hq, cfg.hkv, cfg.d, code, 1), dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty((cfg.hq, T), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    per_kernel = {}
+
+    def step(record):
+        binding.varlen_attn_fwd(q, k, v, cu, ml, cfg.scale, workspace=ws_f, out=o, lse=lse)
+        tf = binding.kernel_times() if record else []
+        binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, cfg.scale, workspace=ws_b, dq=dq, dk=dk, dv=dv)
+        tb = binding.kernel_times() if record else []
+        for name, ms in tf + tb:
+            per_kernel.setdefault(name, []).append(ms)
+
+    for _ in range(warmup):
+        step(False)
+    torch.cuda.synchronize()
+    # timed region: exactly `steps` steps, per-kernel HIP events recorded on the launch stream
+    binding.enable_kernel_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    binding.enable_kernel_timing(False)
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    pairs = wl.causal_pairs(lengths)
+    kernels = {n: sum(x) / len(x) for n, x in per_kernel.items()}
+    return cfg, lengths, pairs, ms_per_step, kernels
+
+
+def cpu_baseline(cid):
+    """The fp64 oracle, as it stands, on a bounded sample of the workload: the sequences of the
+    configuration no longer than 2048 tokens, all heads, forward + backward."""
+    import numpy as np
+    from oracle import attn_oracle as orc
+    from paper_2412_07894_amd import workloads as wl
+    cfg = wl.CONFIGS[cid]
+    lengths = wl.seqlens(cid)
+    keep = [L for L in lengths if L <= 2048]
+    budget_pairs = 1.7e8 / cfg.hq             # about 3e11 flop: 10-30 s of CPU work
+    sample, acc = [], 0
+    for L in sorted(keep, reverse=True):
+        if acc + L * (L + 1) // 2 > budget_pairs and sample:
+            continue
+        sample.append(L)
+        acc += L * (L + 1) // 2
+    cu, q, k, v, do = wl.custom(sample, cfg.hq, cfg.hkv, cfg.d, cfg.dtype, seed=77)
+    t0 = time.perf_counter()
+    orc.fwd(q, k, v, cu, cfg.scale)
+    orc.bwd(q, k, v, do, cu, cfg.scale)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * cfg.d * cfg.hq * wl.causal_pairs(sample)
+    return {
+        "value": flops / dt / 1e12, "unit": "useful TFLOP/s", "cores": orc.threads(), "kind": "oracle",
+        "sample": f"fp64 oracle fwd+bwd on {len(sample)} of the {len(lengths)} sequences of config {cid} "
+                  f"(those <= 2048 tokens, {int(sum(sample))} of {cfg.total_tokens} tokens), all {cfg.hq} heads, "
+                  f"{dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a single-GPU hot path (no collectives, no sharding); run with --gpus 1")
+
+    cfg, lengths, pairs, ms_per_step, kernels = run_gpu(args.config, args.steps, args.warmup)
+    useful = 14.0 * cfg.d * cfg.hq * pairs
+    value = useful / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "packed varlen attn fwd+bwd useful TFLOP/s + % of bf16 MFMA peak, 1 GPU",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "config": {"workload": f"config {cfg.cid}: {cfg.name}", "total_tokens": cfg.total_tokens,
+                   "num_seqs": len(lengths), "max_seqlen": int(max(lengths)), "hq": cfg.hq, "hkv": cfg.hkv,
+                   "head_dim": cfg.d, "causal_pairs": pairs, "useful_flop_per_step": useful},
+        "kernel_ms": kernels,
+    }
+    # dominant kernel: dK/dV.  Algorithmic work = the three products only it provides
+    # (dV = P^T dO, dP = dO V^T, dK = dS^T Q): 6 * d * Hq flop per causal pair.
+    dom = "bwd_dkdv_bf16" if cfg.dtype == "bf16" else "bwd_dkdv_fp32"
+    if dom in kernels and kernels[dom] > 0:
+        alg = 6.0 * cfg.d * cfg.hq * pairs
+        ach = alg / (kernels[dom] * 1e-3) / 1e12
+        peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3
+        out["roofline"] = {"kernel": dom, "bound": "mfma" if cfg.dtype == "bf16" else "alu", "achieved": ach,
+                           "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                           "avg_ms": kernels[dom]}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,110 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+sizes its workspace sanely and rejects bad arguments before touching the GPU (none of these
+calls launches anything, so they run on a host without a GPU)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2412_07894_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hyd_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hyd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2412_07894_amd import binding
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_workspace_bytes(lib):
+    from paper_2412_07894_amd import binding as b
+    f = b.workspace_bytes(16384, 8, 32, 32, 128, b.HYD_BF16, False)
+    w = b.workspace_bytes(16384, 8, 32, 32, 128, b.HYD_BF16, True)
+    assert f > 0 and f % 256 == 0 and w >= f + 4 * 16384 * 32          # backward adds D[Hq][T]
+    assert b.workspace_bytes(16384, 8, 32, 5, 128, b.HYD_BF16, False) == 0   # 32 % 5
+    assert b.workspace_bytes(16384, 8, 32, 32, 96, b.HYD_BF16, False) == 0   # head_dim
+    assert b.workspace_bytes(-1, 8, 32, 32, 128, b.HYD_BF16, False) == 0
+    assert b.workspace_bytes(0, 0, 2, 2, 64, b.HYD_FP32, True) > 0
+
+
+def call_fwd(lib, **kw):
+    a = dict(q=1 << 20, k=1 << 20, v=1 << 20, cu=1 << 20, nseq=2, cu_host=None, T=256, max_len=200, hq=4, hkv=2,
+             d=128, scale=0.1, dt=0, o=1 << 20, lse=1 << 20, ws=1 << 20, ws_bytes=1 << 30, stream=None)
+    a.update(kw)
+    return lib.hyd_varlen_attn_fwd(a["q"], a["k"], a["v"], a["cu"], a["nseq"], a["cu_host"], a["T"], a["max_len"],
+                                   a["hq"], a["hkv"], a["d"], a["scale"], a["dt"], a["o"], a["lse"], a["ws"],
+                                   a["ws_bytes"], a["stream"])
+
+
+def host_cu(vals):
+    arr = (ctypes.c_int32 * len(vals))(*vals)
+    return arr, ctypes.cast(arr, ctypes.c_void_p)
+
+
+def test_forward_argument_errors(lib):
+    """Fake non-NULL device pointers are never dereferenced: every case fails validation first."""
+    OK, NULL, SHAPE, DTYPE, HEADS, HEADDIM, SEQLENS, WORKSPACE = range(8)
+    assert call_fwd(lib, dt=7) == DTYPE
+    assert call_fwd(lib, T=-1) == SHAPE
+    assert call_fwd(lib, nseq=-2) == SHAPE
+    assert call_fwd(lib, nseq=0) == SHAPE                       # tokens that belong to no sequence
+    assert call_fwd(lib, hq=0) == HEADS
+    assert call_fwd(lib, hq=4, hkv=3) == HEADS
+    assert call_fwd(lib, d=96) == HEADDIM
+    assert call_fwd(lib, d=64) == HEADDIM                       # bf16 path is head_dim 128 only
+    assert call_fwd(lib, cu=None) == NULL
+    assert call_fwd(lib, max_len=0) == SHAPE
+    assert call_fwd(lib, max_len=257) == SHAPE
+    keep, p = host_cu([0, 100, 250]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # does not end at T
+    keep, p = host_cu([1, 100, 256]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # does not start at 0
+    keep, p = host_cu([0, 260, 256]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # decreasing
+    keep, p = host_cu([0, 50, 256]);   assert call_fwd(lib, cu_host=p) == SHAPE       # longest 206 > max_len 200
+    assert call_fwd(lib, ws=None) == WORKSPACE
+    assert call_fwd(lib, ws=(1 << 20) + 8) == WORKSPACE         # misaligned
+    assert call_fwd(lib, ws_bytes=16) == WORKSPACE
+    assert call_fwd(lib, q=None) == NULL
+    assert call_fwd(lib, lse=None) == NULL
+    # empty problems are no-ops that need no pointers at all
+    assert call_fwd(lib, T=0, nseq=0, q=None, k=None, v=None, cu=None, o=None, lse=None, ws=None, ws_bytes=0, max_len=0) == OK
+    assert call_fwd(lib, T=0, nseq=3, q=None, k=None, v=None, cu=None, o=None, lse=None, ws=None, ws_bytes=0, max_len=0) == OK
+
+
+def test_backward_argument_errors(lib):
+    def bwd(**kw):
+        a = dict(q=1 << 20, k=1 << 20, v=1 << 20, o=1 << 20, lse=1 << 20, do=1 << 20, cu=1 << 20, nseq=2, cu_host=None,
+                 T=256, max_len=200, hq=4, hkv=2, d=128, scale=0.1, dt=0, dq=1 << 20, dk=1 << 20, dv=1 << 20,
+                 ws=1 << 20, ws_bytes=1 << 30, stream=None)
+        a.update(kw)
+        return lib.hyd_varlen_attn_bwd(a["q"], a["k"], a["v"], a["o"], a["lse"], a["do"], a["cu"], a["nseq"], a["cu_host"],
+                                       a["T"], a["max_len"], a["hq"], a["hkv"], a["d"], a["scale"], a["dt"], a["dq"],
+                                       a["dk"], a["dv"], a["ws"], a["ws_bytes"], a["stream"])
+    from paper_2412_07894_amd import binding as b
+    assert bwd(do=None) == 1 and bwd(dv=None) == 1 and bwd(lse=None) == 1
+    assert bwd(hkv=3) == 4 and bwd(d=100, dt=1) == 5 and bwd(dt=-1) == 3
+    fwd_bytes = b.workspace_bytes(256, 2, 4, 2, 128, 0, False)
+    assert bwd(ws_bytes=fwd_bytes) == 7                          # the backward needs the larger workspace
+    assert bwd(T=0, nseq=0, max_len=0, ws=None, ws_bytes=0) == 0
+
+
+def test_status_strings(lib):
+    from paper_2412_07894_amd import binding as b
+    seen = {b.status_string(c) for c in range(10)}
+    assert len(seen) == 10 and all(s.startswith("HYD_") for s in seen)
+    assert "unknown" in b.status_string(99)
