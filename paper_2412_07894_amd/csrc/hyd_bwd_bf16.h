@@ -6,6 +6,8 @@
 // product D[a][b] then has the A fragment's lane index as its row and B's as its column, and an
 // accumulator in turn is a fragment whose lane index is the column and whose slots are rows.
 #pragma once
+#include <type_traits>
+
 #include "hyd_sched.h"
 
 namespace hyd {
@@ -75,17 +77,16 @@ constexpr int kDqTileBytes = kDqBN * kRowBytes;
 constexpr int kDqLds = 4 * kDqTileBytes + 64;
 
 template <bool MASK>
-__device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, int kb, const bf16x8 (&qf)[8],
-                                         const bf16x8 (&dof)[8], f32x16 (&acc)[4], float scale_log2,
-                                         float lse2, float Dq, int key0, int qrow, int lane) {
-    const int l32 = lane & 31, half = lane >> 5;
+__device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, const FragAddr& fa, int kb,
+                                         const bf16x8 (&qf)[8], const bf16x8 (&dof)[8], f32x16 (&acc)[4],
+                                         float scale_log2, float lse2, float Dq, int key0, int qrow, int half) {
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_row_frag(Kt, 32 * kb + l32, ks, half), qf[ks], s);
+    for (int ks = 0; ks < 8; ++ks) s = mfma32(frag_row(Kt, fa, kb, ks), qf[ks], s);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_row_frag(Vt, 32 * kb + l32, ks, half), dof[ks], dp);
+    for (int ks = 0; ks < 8; ++ks) dp = mfma32(frag_row(Vt, fa, kb, ks), dof[ks], dp);
     uint32_t pk[8];
 #pragma unroll
     for (int r = 0; r < 16; r += 2) {
@@ -105,7 +106,7 @@ __device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, int kb,
         const bf16x8 dsb = as_bf16x8(dv);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
-            acc[db] = mfma32(lds_col_frag(Kt, 2 * kb + b2, db, lane), dsb, acc[db]);
+            acc[db] = mfma32(frag_col(Kt, fa, 2 * kb + b2, db), dsb, acc[db]);
     }
 }
 
@@ -118,6 +119,17 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
+
+    FragAddr fa;
+    fa.init(lane);
+    TileMover<kDqBN, kDqThreads> mk, mv;
+    mk.init(tid, (uint32_t)kv_stride * 2);
+    mv.init(tid, (uint32_t)kv_stride * 2);
+    const uint32_t tile_bytes = kDqBN * (uint32_t)kv_stride * 2;
+    // scale * s = |scale| * (-s): a negative scale flips the sign bits of the Q fragments, which
+    // only the score product reads
+    const float scale_log2 = fabsf(p.scale_log2);
+    const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
 
     WorkFetcher wf;
     wf.init();
@@ -132,6 +144,9 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
         const int wrow0 = q0 + 32 * wave;
         const int qrow = wrow0 + l32;
         const bool qvalid = qrow < L;
+        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * (uint32_t)kv_stride * 2 + kRowBytes;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
 
         bf16x8 qf[8], dof[8];
         float lse2 = 0.f, Dq = 0.f;
@@ -144,7 +159,7 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
                     a = *reinterpret_cast<const u32x4*>(p.q + off + 16 * ks);
                     b = *reinterpret_cast<const u32x4*>(p.d_o + off + 16 * ks);
                 }
-                qf[ks] = as_bf16x8(a);
+                qf[ks] = as_bf16x8(a ^ sign_flip);
                 dof[ks] = as_bf16x8(b);
             }
             if (qvalid) {
@@ -158,19 +173,19 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-        TileMover<kDqBN, kDqThreads> mk, mv;
-        mk.load(p.k, kv_stride, g, row0, row0 + kv_end, tid);
-        mv.load(p.v, kv_stride, g, row0, row0 + kv_end, tid);
-        mk.store(smem, tid);
-        mv.store(smem + kDqTileBytes, tid);
+        mk.load(rk, 0);
+        mv.load(rv, 0);
+        mk.store(smem);
+        mv.store(smem + kDqTileBytes);
         __syncthreads();
-        for (int kt = 0; kt < n_kt; ++kt) {
-            char* Kt = smem + (kt & 1) * 2 * kDqTileBytes;
-            char* Vt = Kt + kDqTileBytes;
+        auto step = [&](auto buf_tag, int kt) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            const char* Kt = smem + BUF * 2 * kDqTileBytes;
+            const char* Vt = Kt + kDqTileBytes;
             const bool more = kt + 1 < n_kt;
             if (more) {
-                mk.load(p.k, kv_stride, g, row0 + (kt + 1) * kDqBN, row0 + kv_end, tid);
-                mv.load(p.v, kv_stride, g, row0 + (kt + 1) * kDqBN, row0 + kv_end, tid);
+                mk.load(rk, (uint32_t)(kt + 1) * tile_bytes);
+                mv.load(rv, (uint32_t)(kt + 1) * tile_bytes);
             }
             const int key0 = kt * kDqBN;
 #pragma unroll
@@ -178,17 +193,21 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
                 const int kfirst = key0 + 32 * kb;
                 if (kfirst <= wrow0 + 31) {
                     if (kfirst + 31 > wrow0)
-                        dq_block<true>(Kt, Vt, kb, qf, dof, acc, p.scale_log2, lse2, Dq, key0, qrow, lane);
+                        dq_block<true>(Kt, Vt, fa, kb, qf, dof, acc, scale_log2, lse2, Dq, key0, qrow, half);
                     else
-                        dq_block<false>(Kt, Vt, kb, qf, dof, acc, p.scale_log2, lse2, Dq, key0, qrow, lane);
+                        dq_block<false>(Kt, Vt, fa, kb, qf, dof, acc, scale_log2, lse2, Dq, key0, qrow, half);
                 }
             }
             if (more) {
-                char* Kn = smem + ((kt + 1) & 1) * 2 * kDqTileBytes;
-                mk.store(Kn, tid);
-                mv.store(Kn + kDqTileBytes, tid);
+                char* Kn = smem + (BUF ^ 1) * 2 * kDqTileBytes;
+                mk.store(Kn);
+                mv.store(Kn + kDqTileBytes);
             }
             __syncthreads();
+        };
+        for (int kt = 0; kt < n_kt; kt += 2) {
+            step(std::integral_constant<int, 0>{}, kt);
+            if (kt + 1 < n_kt) step(std::integral_constant<int, 1>{}, kt + 1);
         }
         if (qvalid)
             store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
@@ -212,17 +231,17 @@ constexpr int kKvLds = 2 * kKvStage + 64;
 
 template <bool MASK>
 __device__ __forceinline__ void dkdv_block(const char* Qt, const char* dOt, const float* lse2_t,
-                                           const float* D_t, int ib, const bf16x8 (&kf)[8],
-                                           const bf16x8 (&vf)[8], f32x16 (&acc_dk)[4], f32x16 (&acc_dv)[4],
-                                           float scale_log2, int qt0, int key, int lane) {
-    const int l32 = lane & 31, half = lane >> 5;
+                                           const float* D_t, const FragAddr& fa, int ib,
+                                           const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
+                                           f32x16 (&acc_dk)[4], f32x16 (&acc_dv)[4], float scale_log2,
+                                           int qt0, int key, int half) {
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_row_frag(Qt, 32 * ib + l32, ks, half), kf[ks], s);
+    for (int ks = 0; ks < 8; ++ks) s = mfma32(frag_row(Qt, fa, ib, ks), kf[ks], s);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_row_frag(dOt, 32 * ib + l32, ks, half), vf[ks], dp);
+    for (int ks = 0; ks < 8; ++ks) dp = mfma32(frag_row(dOt, fa, ib, ks), vf[ks], dp);
     uint32_t pp[8], pd[8];
 #pragma unroll
     for (int rq = 0; rq < 4; ++rq) {
@@ -247,8 +266,8 @@ __device__ __forceinline__ void dkdv_block(const char* Qt, const char* dOt, cons
         const bf16x8 pfr = as_bf16x8(a), dsfr = as_bf16x8(b);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            acc_dv[db] = mfma32(lds_col_frag(dOt, 2 * ib + b2, db, lane), pfr, acc_dv[db]);
-            acc_dk[db] = mfma32(lds_col_frag(Qt, 2 * ib + b2, db, lane), dsfr, acc_dk[db]);
+            acc_dv[db] = mfma32(frag_col(dOt, fa, 2 * ib + b2, db), pfr, acc_dv[db]);
+            acc_dk[db] = mfma32(frag_col(Qt, fa, 2 * ib + b2, db), dsfr, acc_dk[db]);
         }
     }
 }
@@ -262,6 +281,16 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
+
+    FragAddr fa;
+    fa.init(lane);
+    TileMover<kKvBM, kKvThreads> mq, mdo;
+    mq.init(tid, (uint32_t)q_stride * 2);
+    mdo.init(tid, (uint32_t)q_stride * 2);
+    const uint32_t tile_bytes = kKvBM * (uint32_t)q_stride * 2;       // one Q/dO tile in global memory
+    // a negative scale flips the sign bits of the K fragments, which only the score product reads
+    const float scale_log2 = fabsf(p.scale_log2);
+    const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
 
     WorkFetcher wf;
     wf.init();
@@ -277,6 +306,7 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
         const int qt_first = j0 / kKvBM;                      // first query tile that sees key j0
         const int n_qt = (L + kKvBM - 1) / kKvBM - qt_first;
         const int n_iter = n_qt * G;
+        const uint32_t q_bytes = (uint32_t)(L - 1) * (uint32_t)q_stride * 2 + kRowBytes;
 
         bf16x8 kf[8], vf[8];
         {
@@ -288,7 +318,7 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
                     a = *reinterpret_cast<const u32x4*>(p.k + off + 16 * ks);
                     b = *reinterpret_cast<const u32x4*>(p.v + off + 16 * ks);
                 }
-                kf[ks] = as_bf16x8(a);
+                kf[ks] = as_bf16x8(a ^ sign_flip);
                 vf[ks] = as_bf16x8(b);
             }
         }
@@ -298,13 +328,13 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc_dk[db][r] = 0.f; acc_dv[db][r] = 0.f; }
 
-        TileMover<kKvBM, kKvThreads> mq, mdo;
         float stat = 0.f;                                     // threads 0..63: lse2, 64..127: D
         auto stage_load = [&](int it) {
             const int h = g * G + it / n_qt;
             const int qt0 = (qt_first + it % n_qt) * kKvBM;
-            mq.load(p.q, q_stride, h, row0 + qt0, row0 + L, tid);
-            mdo.load(p.d_o, q_stride, h, row0 + qt0, row0 + L, tid);
+            const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * kHeadDim;
+            mq.load(make_rsrc(p.q + base, q_bytes), (uint32_t)(qt0 / kKvBM) * tile_bytes);
+            mdo.load(make_rsrc(p.d_o + base, q_bytes), (uint32_t)(qt0 / kKvBM) * tile_bytes);
             if (tid < 2 * kKvBM) {
                 const int i = qt0 + (tid & (kKvBM - 1));
                 const bool is_lse = tid < kKvBM;
@@ -315,17 +345,17 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
                 }
             }
         };
-        auto stage_store = [&](int buf) {
-            char* base = smem + buf * kKvStage;
-            mq.store(base, tid);
-            mdo.store(base + kKvTileBytes, tid);
+        auto stage_store = [&](char* base) {
+            mq.store(base);
+            mdo.store(base + kKvTileBytes);
             if (tid < 2 * kKvBM) reinterpret_cast<float*>(base + 2 * kKvTileBytes)[tid] = stat;
         };
         stage_load(0);
-        stage_store(0);
+        stage_store(smem);
         __syncthreads();
-        for (int it = 0; it < n_iter; ++it) {
-            const char* base = smem + (it & 1) * kKvStage;
+        auto step = [&](auto buf_tag, int it) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            const char* base = smem + BUF * kKvStage;
             const char* Qt = base;
             const char* dOt = base + kKvTileBytes;
             const float* lse2_t = reinterpret_cast<const float*>(base + 2 * kKvTileBytes);
@@ -338,13 +368,17 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
                 const int ifirst = qt0 + 32 * ib;             // first query row of the block
                 if (ifirst + 31 >= wkey0) {                   // some row sees some key of the wave
                     if (ifirst < wkey0 + 31)
-                        dkdv_block<true>(Qt, dOt, lse2_t, D_t, ib, kf, vf, acc_dk, acc_dv, p.scale_log2, qt0, key, lane);
+                        dkdv_block<true>(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2, qt0, key, half);
                     else
-                        dkdv_block<false>(Qt, dOt, lse2_t, D_t, ib, kf, vf, acc_dk, acc_dv, p.scale_log2, qt0, key, lane);
+                        dkdv_block<false>(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2, qt0, key, half);
                 }
             }
-            if (more) stage_store((it + 1) & 1);
+            if (more) stage_store(smem + (BUF ^ 1) * kKvStage);
             __syncthreads();
+        };
+        for (int it = 0; it < n_iter; it += 2) {
+            step(std::integral_constant<int, 0>{}, it);
+            if (it + 1 < n_iter) step(std::integral_constant<int, 1>{}, it + 1);
         }
         if (kvalid) {
             const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim;

@@ -58,71 +58,95 @@ __device__ __forceinline__ int tile_off(int row, int chunk) {     // byte offset
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-// Operand fragment whose contraction index is the head dimension: 8 consecutive elements
-// [16*ks + 8*half, +8) of row `row` of a tile.
-__device__ __forceinline__ bf16x8 lds_row_frag(const char* tile, int row, int ks, int half) {
-    return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + tile_off(row, 2 * ks + half)));
-}
-
 // Transposing read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane i supplies the
 // address of a 4-element row fragment; lane L then receives element L % 4 of the fragments
 // supplied by lanes L / 4, 4 + L / 4, 8 + L / 4, 12 + L / 4.  With lane i pointing at
 // tile[row0 + i / 4][col0 + 4 * (i % 4) ..+4], lane L ends up with tile[row0 + 0..3][col0 + L]:
 // four consecutive ROWS of one column, i.e. a fragment whose contraction index is the row.
-__device__ __forceinline__ u32x2 lds_tr4(const char* tile, int row0, int col0, int lane16) {
-    const int row = row0 + (lane16 >> 2);
-    const int col = col0 + ((lane16 & 3) << 2);               // element column, multiple of 4
-    const char* p = tile + tile_off(row, col >> 3) + ((col & 4) << 1);
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    u32x2 r;
-    __builtin_memcpy(&r, &v, 8);
-    return r;
+//
+// A column fragment (contraction index = tile row) is two such reads, matched to the accumulator
+// lane map: for contraction step b (16 rows) and column block cb (32 columns) the lane holding
+// column 32*cb + l%32 receives rows 16b + 4*half + {0..3} and 16b + 8 + 4*half + {0..3}, which are
+// the rows that the lane's accumulator registers 8*(b%2) .. +8 of row block b/2 hold (see mfma32).
+
+// Per-lane LDS byte offsets of the two fragment kinds, computed once per kernel.  A fragment read
+// is then one LDS instruction whose address is one of these registers plus a compile-time offset
+// (tile base, 32-row block, 16-row contraction step): swz() is invariant under adding multiples
+// of 16 rows, so blocks and steps move the address by plain multiples of kRowBytes.
+struct FragAddr {
+    uint32_t row[8];      // row fragment of row (lane % 32), contraction step ks = 0..7
+    uint32_t col[8];      // [2 * cb + hi]: transposing read of column block cb, row group hi, step 0
+    __device__ __forceinline__ void init(int lane) {
+        const int l32 = lane & 31, half = lane >> 5, lane16 = lane & 15;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) row[ks] = tile_off(l32, 2 * ks + half);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                const int r = 4 * half + 8 * hi + (lane16 >> 2);
+                const int c = 32 * cb + (lane & 16) + ((lane16 & 3) << 2);
+                col[2 * cb + hi] = tile_off(r, c >> 3) + ((c & 4) << 1);
+            }
+        }
+    }
+};
+
+// Row fragment (contraction index = head dimension): elements [16*ks + 8*half, +8) of tile row
+// 32*blk + lane%32.
+__device__ __forceinline__ bf16x8 frag_row(const char* tile, const FragAddr& fa, int blk, int ks) {
+    return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + fa.row[ks] + blk * 32 * kRowBytes));
 }
 
-// Operand fragment whose contraction index is the tile ROW, matched to the accumulator lane map:
-// for contraction step b (16 rows) and column block cb (32 columns) the lane holding column
-// 32*cb + l%32 receives rows 16b + 4*half + {0..3} and 16b + 8 + 4*half + {0..3}; these are the
-// rows a lane's accumulator registers 8*(b%2) .. +8 of row block b/2 hold (see mfma32).
-__device__ __forceinline__ bf16x8 lds_col_frag(const char* tile, int b, int cb, int lane) {
-    const int half = lane >> 5, lane16 = lane & 15;
-    const int col0 = 32 * cb + (lane & 16);
-    u32x2 lo = lds_tr4(tile, 16 * b + 4 * half, col0, lane16);
-    u32x2 hi = lds_tr4(tile, 16 * b + 8 + 4 * half, col0, lane16);
-    u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+// Column fragment (contraction index = tile row): step b (16 rows), column
+// block cb (32 columns).
+__device__ __forceinline__ bf16x8 frag_col(const char* tile, const FragAddr& fa, int b, int cb) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.col[2 * cb] + b * 16 * kRowBytes));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.col[2 * cb + 1] + b * 16 * kRowBytes));
+    u32x2 l2, h2;
+    __builtin_memcpy(&l2, &lo, 8);
+    __builtin_memcpy(&h2, &hi, 8);
+    u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
     return as_bf16x8(v);
 }
 
-// Global -> registers -> LDS copy of a [ROWS][128] bf16 tile by NT threads.  Row r of the tile is
-// global row (row_base + r) of a [T][H][128] tensor at head `h`; rows at or beyond row_end are
-// filled with zeros (never read from memory).
+// Buffer resource over `bytes` bytes starting at `base`: loads beyond the range return zero, which
+// is how the tails of a sequence are zero-filled without branches.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// Global -> registers -> LDS copy of a [ROWS][128] bf16 tile by NT threads.  Thread t moves the
+// 16-byte chunks (row t/16 + 16*p, chunk t%16), p = 0..ROWS/16*... ; rows beyond the buffer
+// resource's range arrive as zeros.
 template <int ROWS, int NT>
 struct TileMover {
     static constexpr int kChunks = ROWS * kChunksPerRow;
     static constexpr int kPerThread = kChunks / NT;
+    static constexpr int kRowStep = NT / kChunksPerRow;          // rows between a thread's chunks
     static_assert(kChunks % NT == 0, "tile must divide over the threads");
+    static_assert(kRowStep % 16 == 0, "swz() must not change between a thread's chunks");
     u32x4 reg[kPerThread];
+    uint32_t voff;        // byte offset of (row t/16, chunk t%16) from the resource base
+    uint32_t lds_off;     // LDS byte offset of the same chunk within a tile
+    uint32_t step_bytes;  // kRowStep rows in bytes
 
-    __device__ __forceinline__ void load(const uint16_t* base, int64_t row_stride_elems, int h,
-                                         int row_base, int row_end, int tid) {
-#pragma unroll
-        for (int p = 0; p < kPerThread; ++p) {
-            const int idx = tid + p * NT;
-            const int r = idx / kChunksPerRow, c = idx % kChunksPerRow;
-            const int grow = row_base + r;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (grow < row_end)
-                v = *reinterpret_cast<const u32x4*>(base + (int64_t)grow * row_stride_elems +
-                                                   (int64_t)h * kHeadDim + c * 8);
-            reg[p] = v;
-        }
+    __device__ __forceinline__ void init(int tid, uint32_t row_stride_bytes) {
+        const int r = tid / kChunksPerRow, c = tid % kChunksPerRow;
+        voff = r * row_stride_bytes + c * 16;
+        lds_off = tile_off(r, c);
+        step_bytes = kRowStep * row_stride_bytes;
     }
-    __device__ __forceinline__ void store(char* tile, int tid) const {
+    // tile_byte_off: byte offset of the tile's first row from the resource base (wave-uniform)
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, uint32_t tile_byte_off) {
 #pragma unroll
-        for (int p = 0; p < kPerThread; ++p) {
-            const int idx = tid + p * NT;
-            const int r = idx / kChunksPerRow, c = idx % kChunksPerRow;
-            *reinterpret_cast<u32x4*>(tile + tile_off(r, c)) = reg[p];
-        }
+        for (int p = 0; p < kPerThread; ++p)
+            reg[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, tile_byte_off + p * step_bytes, 0);
+    }
+    __device__ __forceinline__ void store(char* tile) const {
+#pragma unroll
+        for (int p = 0; p < kPerThread; ++p)
+            *reinterpret_cast<u32x4*>(tile + lds_off + p * kRowStep * kRowBytes) = reg[p];
     }
 };
 

@@ -13,6 +13,8 @@
 // (contraction index = key = accumulator row), while V^T fragments come out of the row-major V
 // tile with the transposing LDS read.
 #pragma once
+#include <type_traits>
+
 #include "hyd_sched.h"
 
 namespace hyd {
@@ -33,10 +35,9 @@ struct FwdParams {
 };
 
 template <bool MASK>
-__device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const bf16x8 (&qf)[8],
-                                         f32x16 (&acc_o)[4], float& m_run, float& l_run,
-                                         float scale_log2, int key0, int qrow, int lane) {
-    const int l32 = lane & 31, half = lane >> 5;
+__device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const FragAddr& fa,
+                                         const bf16x8 (&qf)[8], f32x16 (&acc_o)[4], float& m_run,
+                                         float& l_run, float scale_log2, int key0, int qrow, int half) {
     f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -45,14 +46,20 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const b
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            bf16x8 a = lds_row_frag(Kt, 32 * kb + l32, ks, half);
-            s[kb] = mfma32(a, qf[ks], s[kb]);
-        }
+#ifdef HYD_ABL_NOLDS_K
+        for (int kb = 0; kb < 2; ++kb) s[kb] = mfma32(frag_row(Kt, fa, kb, 0), qf[ks], s[kb]);
+#else
+        for (int kb = 0; kb < 2; ++kb) s[kb] = mfma32(frag_row(Kt, fa, kb, ks), qf[ks], s[kb]);
+#endif
     }
-    const bool neg = scale_log2 < 0.f;
-    // row extreme of the raw scores over visible keys
-    float mx = neg ? INFINITY : -INFINITY;
+#ifdef HYD_ABL_NOSOFTMAX
+    uint32_t pk[2][8];
+    for (int kb = 0; kb < 2; ++kb) for (int r = 0; r < 16; r += 2) pk[kb][r >> 1] = pack_bf16(s[kb][r], s[kb][r + 1]);
+    l_run += 1.f; m_run = 0.f;
+#else
+    // row maximum of the raw scores over visible keys (scale_log2 >= 0 here: a negative softmax
+    // scale has been folded into the sign of the Q fragments)
+    float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -60,15 +67,12 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const b
             float x = s[kb][r];
             if (MASK) {
                 const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (key > qrow) x = neg ? INFINITY : -INFINITY;
+                if (key > qrow) x = -INFINITY;
             }
-            mx = neg ? fminf(mx, x) : fmaxf(mx, x);
+            mx = fmaxf(mx, x);
         }
     }
-    {
-        const float other = shfl_xor32(mx);
-        mx = neg ? fminf(mx, other) : fmaxf(mx, other);
-    }
+    mx = fmaxf(mx, shfl_xor32(mx));
     const float m_new = fmaxf(m_run, mx * scale_log2);
     if (__any(m_new > m_run)) {         // rescale only when some row's maximum moved
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -98,16 +102,19 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const b
         }
     }
     l_run += lsum;
+#endif
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         u32x4 pv = {pk[b >> 1][4 * (b & 1) + 0], pk[b >> 1][4 * (b & 1) + 1],
                     pk[b >> 1][4 * (b & 1) + 2], pk[b >> 1][4 * (b & 1) + 3]};
         const bf16x8 pb = as_bf16x8(pv);
+#ifdef HYD_ABL_NOLDS_V
+        const bf16x8 va = frag_col(Vt, fa, b, 0);
+        for (int db = 0; db < 4; ++db) acc_o[db] = mfma32(va, pb, acc_o[db]);
+#else
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            bf16x8 a = lds_col_frag(Vt, b, db, lane);
-            acc_o[db] = mfma32(a, pb, acc_o[db]);
-        }
+        for (int db = 0; db < 4; ++db) acc_o[db] = mfma32(frag_col(Vt, fa, b, db), pb, acc_o[db]);
+#endif
     }
 }
 
@@ -120,6 +127,16 @@ __global__ void __launch_bounds__(kFwdThreads, 2) hyd_fwd_bf16_kernel(FwdParams 
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
+
+    FragAddr fa;
+    fa.init(lane);
+    TileMover<kFwdBN, kFwdThreads> mk, mv;
+    mk.init(tid, (uint32_t)kv_stride * 2);
+    mv.init(tid, (uint32_t)kv_stride * 2);
+    const uint32_t tile_bytes = kFwdBN * (uint32_t)kv_stride * 2;     // one K/V tile in global memory
+    // scale * s = |scale| * (-s): a negative scale flips the sign bits of the Q fragments instead
+    const float scale_log2 = fabsf(p.scale_log2);
+    const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
 
     WorkFetcher wf;
     wf.init();
@@ -134,6 +151,10 @@ __global__ void __launch_bounds__(kFwdThreads, 2) hyd_fwd_bf16_kernel(FwdParams 
         const int wrow0 = q0 + 32 * wave;                 // first query row of this wave
         const int qrow = wrow0 + l32;
         const bool qvalid = qrow < L;
+        // K/V rows [0, kv_end) of this sequence and KV head; reads past them return zero
+        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * (uint32_t)kv_stride * 2 + kRowBytes;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
 
         bf16x8 qf[8];
         {
@@ -142,7 +163,7 @@ __global__ void __launch_bounds__(kFwdThreads, 2) hyd_fwd_bf16_kernel(FwdParams 
             for (int ks = 0; ks < 8; ++ks) {
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (qvalid) v = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
-                qf[ks] = as_bf16x8(v);
+                qf[ks] = as_bf16x8(v ^ sign_flip);
             }
         }
         f32x16 acc_o[4];
@@ -152,33 +173,44 @@ __global__ void __launch_bounds__(kFwdThreads, 2) hyd_fwd_bf16_kernel(FwdParams 
             for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
 
-        TileMover<kFwdBN, kFwdThreads> mk, mv;
-        mk.load(p.k, kv_stride, g, row0, row0 + kv_end, tid);
-        mv.load(p.v, kv_stride, g, row0, row0 + kv_end, tid);
-        mk.store(smem, tid);
-        mv.store(smem + kFwdTileBytes, tid);
+        mk.load(rk, 0);
+        mv.load(rv, 0);
+        mk.store(smem);
+        mv.store(smem + kFwdTileBytes);
         __syncthreads();
-        for (int kt = 0; kt < n_kt; ++kt) {
-            char* Kt = smem + (kt & 1) * 2 * kFwdTileBytes;
-            char* Vt = Kt + kFwdTileBytes;
+        // one tile step on LDS buffer BUF (compile-time, so that fragment reads are base+immediate)
+        auto step = [&](auto buf_tag, int kt) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            const char* Kt = smem + BUF * 2 * kFwdTileBytes;
+            const char* Vt = Kt + kFwdTileBytes;
             const bool more = kt + 1 < n_kt;
+#ifndef HYD_ABL_NOSTAGE
             if (more) {
-                mk.load(p.k, kv_stride, g, row0 + (kt + 1) * kFwdBN, row0 + kv_end, tid);
-                mv.load(p.v, kv_stride, g, row0 + (kt + 1) * kFwdBN, row0 + kv_end, tid);
+                mk.load(rk, (uint32_t)(kt + 1) * tile_bytes);
+                mv.load(rv, (uint32_t)(kt + 1) * tile_bytes);
             }
+#endif
             const int key0 = kt * kFwdBN;
             if (key0 <= wrow0 + 31) {                     // some key of the tile is visible to the wave
                 if (key0 + kFwdBN - 1 > wrow0)
-                    fwd_tile<true>(Kt, Vt, qf, acc_o, m_run, l_run, p.scale_log2, key0, qrow, lane);
+                    fwd_tile<true>(Kt, Vt, fa, qf, acc_o, m_run, l_run, scale_log2, key0, qrow, half);
                 else
-                    fwd_tile<false>(Kt, Vt, qf, acc_o, m_run, l_run, p.scale_log2, key0, qrow, lane);
+                    fwd_tile<false>(Kt, Vt, fa, qf, acc_o, m_run, l_run, scale_log2, key0, qrow, half);
             }
+#ifndef HYD_ABL_NOSTAGE
             if (more) {
-                char* Kn = smem + ((kt + 1) & 1) * 2 * kFwdTileBytes;
-                mk.store(Kn, tid);
-                mv.store(Kn + kFwdTileBytes, tid);
+                char* Kn = smem + (BUF ^ 1) * 2 * kFwdTileBytes;
+                mk.store(Kn);
+                mv.store(Kn + kFwdTileBytes);
             }
+#endif
+#ifndef HYD_ABL_NOBARRIER_INLOOP
             __syncthreads();
+#endif
+        };
+        for (int kt = 0; kt < n_kt; kt += 2) {
+            step(std::integral_constant<int, 0>{}, kt);
+            if (kt + 1 < n_kt) step(std::integral_constant<int, 1>{}, kt + 1);
         }
         // epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = l_run + shfl_xor32(l_run);
