@@ -42,7 +42,10 @@ WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
     return w;
 }
 
-int tile_of(hyd_dtype dt) { return dt == HYD_BF16 ? kFwdBM : kF32Tile; }
+// rows per work item of the forward and of the backward kernels
+int tile_fwd(hyd_dtype dt) { return dt == HYD_BF16 ? kFwdBM : kF32Tile; }
+int tile_bwd(hyd_dtype dt) { return dt == HYD_BF16 ? kDqBM : kF32Tile; }
+static_assert(kDqBM == kKvBN, "dQ and dK/dV share one item list");
 
 bool head_dim_ok(hyd_dtype dt, int d) { return dt == HYD_BF16 ? d == 128 : (d == 64 || d == 128); }
 
@@ -201,7 +204,7 @@ size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, i
                                        hyd_dtype dt, int is_bwd) {
     if (total_tokens < 0 || num_seqs < 0 || hq <= 0 || hkv <= 0 || hq % hkv != 0) return 0;
     if ((dt != HYD_BF16 && dt != HYD_FP32) || !head_dim_ok(dt, head_dim)) return 0;
-    return ws_layout(total_tokens, num_seqs, tile_of(dt), hq, is_bwd != 0).total;
+    return ws_layout(total_tokens, num_seqs, is_bwd ? tile_bwd(dt) : tile_fwd(dt), hq, is_bwd != 0).total;
 }
 
 hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
@@ -221,7 +224,7 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (t_timing) timed_clear();
 
-    const int tile = tile_of(dt);
+    const int tile = tile_fwd(dt);
     const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, false);
     const SchedView sv = make_view(static_cast<char*>(workspace), w);
     {
@@ -272,7 +275,7 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (t_timing) timed_clear();
 
-    const int tile = tile_of(dt);
+    const int tile = tile_bwd(dt);
     const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, true);
     char* ws = static_cast<char*>(workspace);
     const SchedView sv = make_view(ws, w);
