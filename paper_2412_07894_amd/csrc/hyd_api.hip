@@ -19,7 +19,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t hdr, hist, cnt_ge, offs, fill, items, dvec, total;
+    size_t hdr, hist, cnt_ge, offs, fill, items, dvec, lse2vec, total;
     int n_lev, max_items;
 };
 
@@ -38,14 +38,19 @@ WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
     w.items = at;  at += align_up(sizeof(int) * 2 * (size_t)w.max_items);
     w.dvec = at;
     if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
+    w.lse2vec = at;
+    if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
     w.total = at;
     return w;
 }
 
 // rows per work item of the forward and of the backward kernels
 int tile_fwd(hyd_dtype dt) { return dt == HYD_BF16 ? kFwdBM : kF32Tile; }
-int tile_bwd(hyd_dtype dt) { return dt == HYD_BF16 ? kDqBM : kF32Tile; }
-static_assert(kDqBM == kKvBN, "dQ and dK/dV share one item list");
+int tile_dq(hyd_dtype dt) { return dt == HYD_BF16 ? kDqBM : kF32Tile; }
+int tile_kv(hyd_dtype dt) { return dt == HYD_BF16 ? kKvBN : kF32Tile; }
+// the backward workspace is laid out for the smaller of its two tile sizes (more items)
+int tile_bwd(hyd_dtype dt) { return tile_dq(dt) < tile_kv(dt) ? tile_dq(dt) : tile_kv(dt); }
+
 
 bool head_dim_ok(hyd_dtype dt, int d) { return dt == HYD_BF16 ? d == 128 : (d == 64 || d == 128); }
 
@@ -275,14 +280,16 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (t_timing) timed_clear();
 
-    const int tile = tile_bwd(dt);
-    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, true);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile_bwd(dt), hq, true);
     char* ws = static_cast<char*>(workspace);
     const SchedView sv = make_view(ws, w);
     float* Dvec = reinterpret_cast<float*>(ws + w.dvec);
+    float* Lse2 = reinterpret_cast<float*>(ws + w.lse2vec);
+    // the item list is built for the dK/dV kernel first and, if the dQ kernel uses another tile
+    // size, rebuilt for it once dK/dV has drained (stream order)
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile, sv);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile_kv(dt), sv);
     }
     const long long n_rows = (long long)total_tokens * hq;
     const long long work_q = (long long)w.max_items * hq, work_kv = (long long)w.max_items * hkv;
@@ -290,13 +297,13 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
         {
             KernelTimer kt("bwd_rowdot_bf16", st);
             hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st,
-                               static_cast<const uint16_t*>(o), static_cast<const uint16_t*>(d_o), Dvec,
+                               static_cast<const uint16_t*>(o), static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2,
                                total_tokens, hq);
         }
         BwdParams p;
         p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
         p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
-        p.lse = lse; p.D = Dvec;
+        p.lse2 = Lse2; p.D = Dvec;
         p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
         p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
@@ -306,6 +313,10 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
             KernelTimer kt("bwd_dkdv_bf16", st);
             hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_kv, work_kv)),
                                dim3(kKvThreads), kKvLds, st, p);
+        }
+        if (tile_dq(dt) != tile_kv(dt)) {
+            KernelTimer kt("schedule_prelude", st);
+            hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile_dq(dt), sv);
         }
         {
             p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);

@@ -13,11 +13,16 @@
 namespace hyd {
 
 // ---------------------------------------------------------------------------------------------
-// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32).  16 lanes per (token, head) row.
+// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32) and LSE2 = LSE * log2(e), the form in which the
+// two backward kernels consume them (P = exp2(s * scale * log2(e) - LSE2)).  16 lanes per row.
 // ---------------------------------------------------------------------------------------------
+constexpr float kLog2e = 1.44269504088896340736f;
+
 __global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t* __restrict__ o,
                                                                  const uint16_t* __restrict__ d_o,
-                                                                 float* __restrict__ D, int T, int hq) {
+                                                                 const float* __restrict__ lse,
+                                                                 float* __restrict__ D, float* __restrict__ lse2,
+                                                                 int T, int hq) {
     const int64_t n_rows = (int64_t)T * hq;
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
@@ -35,12 +40,13 @@ __global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t
     if (row < n_rows && c == 0) {
         const int t = (int)(row / hq), h = (int)(row % hq);
         D[(int64_t)h * T + t] = acc;
+        lse2[(int64_t)h * T + t] = lse[(int64_t)h * T + t] * kLog2e;
     }
 }
 
 struct BwdParams {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
-    const float* lse; const float* D;
+    const float* lse2; const float* D;      // LSE * log2(e) and rowsum(dO * O), both [Hq][T]
     uint16_t* dq; uint16_t* dk; uint16_t* dv;
     const int32_t* cu;
     int T, hq, hkv;
@@ -49,8 +55,6 @@ struct BwdParams {
     HeadMap hm;
     WgTrace tr;
 };
-
-constexpr float kLog2e = 1.44269504088896340736f;
 
 // Writes a transposed accumulator set acc[4] (rows = head dim, column = this lane's token) as one
 // bf16 row fragment: lane (l32, half) owns columns 32*db + 8*rq + 4*half + {0..3}.
@@ -67,69 +71,102 @@ __device__ __forceinline__ void store_rows_bf16(uint16_t* row_ptr, const f32x16 
 }
 
 // ---------------------------------------------------------------------------------------------
-// dQ.  Work item = (sequence, 128-row query tile, query head); wave w owns rows 32w..32w+31.
-// Same orientation as the forward: S^T[key][q] = K Q^T and dP^T[key][q] = V dO^T put one query
-// row in each lane, so LSE_i and D_i are per-lane scalars; dS^T then is the B operand of
-// dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing LDS read of the same K tile.
+// dQ.  Work item = (sequence, query tile of 32*NW rows, query head); wave w owns rows 32w..32w+31.
+// Same orientation, K/V ring and causal structure as the forward kernel: S^T[key][q] = K Q^T and
+// dP^T[key][q] = V dO^T put one query row in each lane, so LSE_i and D_i are per-lane scalars;
+// dS^T then is the B operand of dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing
+// LDS read of the same K tile.
 // ---------------------------------------------------------------------------------------------
-constexpr int kDqBM = 128, kDqBN = 64, kDqThreads = 256;
+#ifndef HYD_DQ_WAVES
+#define HYD_DQ_WAVES 8
+#endif
+constexpr int kDqWaves = HYD_DQ_WAVES;
+constexpr int kDqBM = 32 * kDqWaves, kDqBN = 64, kDqThreads = 64 * kDqWaves;
+constexpr int kDqStages = kDqWaves == 8 ? 3 : 2;
 constexpr int kDqTileBytes = kDqBN * kRowBytes;
-constexpr int kDqLds = 4 * kDqTileBytes + 64;
+constexpr int kDqStageBytes = 2 * kDqTileBytes;
+constexpr int kDqLds = kDqStages * kDqStageBytes + 64;
 
-template <bool MASK>
+typedef __attribute__((address_space(3))) void lds_void_b;
+
+// One 32-key block (rows 32*kb.. of the K and V tiles) for the 32 rows of a wave.  `k0`: key index
+// minus row index of the block's first key for this lane's row if the block needs masking, else a
+// value that masks nothing.
 __device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, const FragAddr& fa, int kb,
                                          const bf16x8 (&qf)[8], const bf16x8 (&dof)[8], f32x16 (&acc)[4],
-                                         float scale_log2, float lse2, float Dq, int key0, int qrow, int half) {
+                                         float scale_log2, float lse2, float Dq, bool mask, int krel) {
+    // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+    {
+        // fragment i < 8: K, contraction step i; i >= 8: V, step i - 8; reads run kAhead ahead
+        constexpr int kAhead = 6;
+        bf16x8 f[kAhead];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = mfma32(frag_row(Kt, fa, kb, ks), qf[ks], s);
+        for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < 8 ? Kt : Vt, fa, kb, i & 7);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = mfma32(frag_row(Vt, fa, kb, ks), dof[ks], dp);
-    uint32_t pk[8];
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-        float t0 = __builtin_fmaf(s[r], scale_log2, -lse2);
-        float t1 = __builtin_fmaf(s[r + 1], scale_log2, -lse2);
-        if (MASK) {
-            const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (key > qrow) t0 = -INFINITY;
-            if (key + 1 > qrow) t1 = -INFINITY;
+        for (int i = 0; i < 16; ++i) {
+            if (i < 8) s = mfma32(f[i % kAhead], qf[i], s);
+            else dp = mfma32(f[i % kAhead], dof[i - 8], dp);
+            if (i + kAhead < 16) f[i % kAhead] = frag_row(i + kAhead < 8 ? Kt : Vt, fa, kb, (i + kAhead) & 7);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        const float p0 = __builtin_amdgcn_exp2f(t0), p1 = __builtin_amdgcn_exp2f(t1);
-        pk[r >> 1] = pack_bf16(p0 * (dp[r] - Dq), p1 * (dp[r + 1] - Dq));
     }
+    constexpr int kCAhead = 4;
+    bf16x8 cf[kCAhead];                       // K^T fragments for the dQ product, requested early
 #pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-        u32x4 dv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
-        const bf16x8 dsb = as_bf16x8(dv);
+    for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(Kt, fa, 2 * kb + (i >> 2), i & 3);
+    __builtin_amdgcn_sched_barrier(0);
+    if (mask) {                               // hidden keys: P = exp2(-inf) = 0
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-            acc[db] = mfma32(frag_col(Kt, fa, 2 * kb + b2, db), dsb, acc[db]);
+        for (int r = 0; r < 16; ++r)
+            if (8 * (r >> 2) + (r & 3) + krel > 0) s[r] = -INFINITY;
+    }
+    auto ds_pair = [&](int j) -> uint32_t {   // scores 2j, 2j+1 of the 16 a lane holds
+        const int r = 2 * j;
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lse2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], scale_log2, -lse2));
+        return pack_bf16(p0 * (dp[r] - Dq), p1 * (dp[r + 1] - Dq));
+    };
+    u32x4 dcur, dnxt;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dcur[e] = ds_pair(e);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {             // i = 4*b2 + db
+        const int b2 = i >> 2, db = i & 3;
+        acc[db] = mfma32(cf[i % kCAhead], as_bf16x8(dcur), acc[db]);
+        if (i + kCAhead < 8) cf[i % kCAhead] = frag_col(Kt, fa, 2 * kb + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
+        if (b2 == 0) dnxt[db] = ds_pair(4 + db);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i == 3) dcur = dnxt;
     }
 }
 
-__global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
+__global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* slot = reinterpret_cast<int*>(smem + 4 * kDqTileBytes);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int* slot = reinterpret_cast<int*>(smem + kDqStages * kDqStageBytes);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
 
     FragAddr fa;
     fa.init(lane);
-    TileMover<kDqBN, kDqThreads> mk, mv;
-    mk.init(tid, (uint32_t)kv_stride * 2);
-    mv.init(tid, (uint32_t)kv_stride * 2);
-    const uint32_t tile_bytes = kDqBN * (uint32_t)kv_stride * 2;
+    const int dma_row = 4 * wave + (lane >> 4);
+    const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t tile_bytes = kDqBN * kv_stride_b;
     // scale * s = |scale| * (-s): a negative scale flips the sign bits of the Q fragments, which
-    // only the score product reads
-    const float scale_log2 = fabsf(p.scale_log2);
+    // only the score product reads; a zero scale becomes an epsilon so that -inf * scale = -inf
+    const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
+    const int krel = 4 * half - l32;
 
     WorkFetcher wf;
     wf.init();
@@ -144,9 +181,23 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
         const int wrow0 = q0 + 32 * wave;
         const int qrow = wrow0 + l32;
         const bool qvalid = qrow < L;
-        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * (uint32_t)kv_stride * 2 + kRowBytes;
+        const bool active = wrow0 < L;
+        const int td = wrow0 / kDqBN;                     // this wave's diagonal (= last) tile
+        const int diag_kb = (wrow0 % kDqBN) / 32;         // its diagonal block within that tile
+        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowBytes;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
+        auto dma_tile = [&](int t, int stage) {
+            char* dst = smem + stage * kDqStageBytes + 4 * wave * kRowBytes;
+#pragma unroll
+            for (int j = 0; j < 16 / kDqWaves; ++j) {
+                const uint32_t soff = (uint32_t)t * tile_bytes + (uint32_t)(j * kDqWaves * 4) * kv_stride_b;
+                char* d = dst + j * kDqWaves * 4 * kRowBytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_b*)d, 16, dma_voff, soff, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_b*)(d + kDqTileBytes), 16, dma_voff, soff, 0, 0);
+            }
+        };
+        dma_tile(0, 0);
 
         bf16x8 qf[8], dof[8];
         float lse2 = 0.f, Dq = 0.f;
@@ -163,7 +214,7 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
                 dof[ks] = as_bf16x8(b);
             }
             if (qvalid) {
-                lse2 = p.lse[(int64_t)head * p.T + row0 + qrow] * kLog2e;
+                lse2 = p.lse2[(int64_t)head * p.T + row0 + qrow];
                 Dq = p.D[(int64_t)head * p.T + row0 + qrow];
             }
         }
@@ -172,42 +223,33 @@ __global__ void __launch_bounds__(kDqThreads, 2) hyd_bwd_dq_bf16_kernel(BwdParam
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+        __syncthreads();                                  // waits for tile 0, then the barrier
 
-        mk.load(rk, 0);
-        mv.load(rv, 0);
-        mk.store(smem);
-        mv.store(smem + kDqTileBytes);
-        __syncthreads();
-        auto step = [&](auto buf_tag, int kt) {
-            constexpr int BUF = decltype(buf_tag)::value;
-            const char* Kt = smem + BUF * 2 * kDqTileBytes;
+        auto step = [&](auto stage_tag, int t) {
+            constexpr int ST = decltype(stage_tag)::value;
+            constexpr int STN = (ST + 1) % kDqStages;
+            const char* Kt = smem + ST * kDqStageBytes;
             const char* Vt = Kt + kDqTileBytes;
-            const bool more = kt + 1 < n_kt;
-            if (more) {
-                mk.load(rk, (uint32_t)(kt + 1) * tile_bytes);
-                mv.load(rv, (uint32_t)(kt + 1) * tile_bytes);
-            }
-            const int key0 = kt * kDqBN;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int kfirst = key0 + 32 * kb;
-                if (kfirst <= wrow0 + 31) {
-                    if (kfirst + 31 > wrow0)
-                        dq_block<true>(Kt, Vt, fa, kb, qf, dof, acc, scale_log2, lse2, Dq, key0, qrow, half);
-                    else
-                        dq_block<false>(Kt, Vt, fa, kb, qf, dof, acc, scale_log2, lse2, Dq, key0, qrow, half);
-                }
-            }
-            if (more) {
-                char* Kn = smem + (BUF ^ 1) * 2 * kDqTileBytes;
-                mk.store(Kn);
-                mv.store(Kn + kDqTileBytes);
+            if (t + 1 < n_kt) dma_tile(t + 1, STN);
+            if (active && t <= td) {
+                const bool diag = t == td;
+                dq_block(Kt, Vt, fa, 0, qf, dof, acc, scale_log2, lse2, Dq, diag && diag_kb == 0, krel);
+                if (!(diag && diag_kb == 0))
+                    dq_block(Kt, Vt, fa, 1, qf, dof, acc, scale_log2, lse2, Dq, diag, krel);
             }
             __syncthreads();
         };
-        for (int kt = 0; kt < n_kt; kt += 2) {
-            step(std::integral_constant<int, 0>{}, kt);
-            if (kt + 1 < n_kt) step(std::integral_constant<int, 1>{}, kt + 1);
+        if (kDqStages == 2) {
+            for (int t = 0; t < n_kt; t += 2) {
+                step(std::integral_constant<int, 0>{}, t);
+                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
+            }
+        } else {
+            for (int t = 0; t < n_kt; t += 3) {
+                step(std::integral_constant<int, 0>{}, t);
+                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
+                if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kDqStages>{}, t + 2);
+            }
         }
         if (qvalid)
             store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
@@ -341,7 +383,7 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
                 stat = is_lse ? INFINITY : 0.f;               // rows past the end: P = exp2(-inf) = 0
                 if (i < L) {
                     const int64_t at = (int64_t)h * p.T + row0 + i;
-                    stat = is_lse ? p.lse[at] * kLog2e : p.D[at];
+                    stat = is_lse ? p.lse2[at] : p.D[at];
                 }
             }
         };
