@@ -259,79 +259,112 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
 
 // ---------------------------------------------------------------------------------------------
 // dK/dV.  Work item = (sequence, 128-key tile, KV head); wave w owns keys 32w..32w+31 and keeps
-// their K and V rows in registers as B fragments.  Query tiles of 64 rows (Q, dO, LSE, D) stream
-// through LDS, for every query head of the KV group in turn, accumulating into the same dK/dV
-// registers.  S[i][j] = Q K^T and dP[i][j] = dO V^T put one KEY in each lane (column) and query
-// rows in the accumulator slots, so P and dS are directly the B fragments (contraction index =
-// query row) of dV^T[d][j] = dO^T P and dK^T[d][j] = Q^T dS, whose A fragments come from the
-// transposing LDS read of the same dO and Q tiles.
+// their K and V rows in registers as B fragments.  Query tiles of 64 rows (Q, dO, LSE2, D) stream
+// through a ring of LDS stages by direct-to-LDS loads, for every query head of the KV group in
+// turn, accumulating into the same dK/dV registers.  S[i][j] = Q K^T and dP[i][j] = dO V^T put
+// one KEY in each lane (column) and query rows in the accumulator slots, so P and dS are directly
+// the B fragments (contraction index = query row) of dV^T[d][j] = dO^T P and dK^T[d][j] = Q^T dS,
+// whose A fragments come from the transposing LDS read of the same dO and Q tiles.
 // ---------------------------------------------------------------------------------------------
-constexpr int kKvBN = 128, kKvBM = 64, kKvThreads = 256;
+constexpr int kKvWaves = 4;
+constexpr int kKvBN = 32 * kKvWaves, kKvBM = 64, kKvThreads = 64 * kKvWaves, kKvStages = 3;
 constexpr int kKvTileBytes = kKvBM * kRowBytes;                       // 16 KB
-constexpr int kKvStage = 2 * kKvTileBytes + 2 * kKvBM * 4;            // Q, dO, lse2, D
-constexpr int kKvLds = 2 * kKvStage + 64;
+constexpr int kKvStageBytes = 2 * kKvTileBytes + 2 * kKvBM * 4;       // Q, dO, LSE2, D
+constexpr int kKvLds = kKvStages * kKvStageBytes + 64;
 
-template <bool MASK>
+// One 32-row query block (rows 32*ib.. of the staged tile) against the 32 keys of a wave.
+// `mask`: the block straddles the diagonal (key > query row is hidden); irel = key - first row.
 __device__ __forceinline__ void dkdv_block(const char* Qt, const char* dOt, const float* lse2_t,
                                            const float* D_t, const FragAddr& fa, int ib,
                                            const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
                                            f32x16 (&acc_dk)[4], f32x16 (&acc_dv)[4], float scale_log2,
-                                           int qt0, int key, int half) {
+                                           bool mask, int irel, int half) {
+    // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+    {
+        // fragment i < 8: Q, contraction step i; i >= 8: dO, step i - 8; reads run kAhead ahead
+        constexpr int kAhead = 6;
+        bf16x8 f[kAhead];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = mfma32(frag_row(Qt, fa, ib, ks), kf[ks], s);
+        for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < 8 ? Qt : dOt, fa, ib, i & 7);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = mfma32(frag_row(dOt, fa, ib, ks), vf[ks], dp);
+        for (int i = 0; i < 16; ++i) {
+            if (i < 8) s = mfma32(f[i % kAhead], kf[i], s);
+            else dp = mfma32(f[i % kAhead], vf[i - 8], dp);
+            if (i + kAhead < 16) f[i % kAhead] = frag_row(i + kAhead < 8 ? Qt : dOt, fa, ib, (i + kAhead) & 7);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // A fragments of the two accumulating products: fragment i = (contraction step i/8, product
+    // (i/4)%2: 0 = dV from dO, 1 = dK from Q, head-dim block i%4), requested kCAhead ahead
+    constexpr int kCAhead = 4;
+    bf16x8 cf[kCAhead];
+#pragma unroll
+    for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(((i >> 2) & 1) ? Qt : dOt, fa, 2 * ib + (i >> 3), i & 3);
+    __builtin_amdgcn_sched_barrier(0);
+    if (mask) {                               // hidden pairs: P = exp2(-inf) = 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (irel > 8 * (r >> 2) + 4 * half + (r & 3)) s[r] = -INFINITY;
+    }
+    // P and dS for query rows 4*rq + 4*half.. of the block, as packed bf16 pairs
     uint32_t pp[8], pd[8];
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
+    auto quad = [&](int rq) {
         const int i0 = 32 * ib + 8 * rq + 4 * half;           // first of 4 consecutive query rows
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2_t + i0);
         const f32x4 d4 = *reinterpret_cast<const f32x4*>(D_t + i0);
         float pv[4], dsv[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            float t = __builtin_fmaf(s[4 * rq + e], scale_log2, -l4[e]);
-            if (MASK) { if (key > qt0 + i0 + e) t = -INFINITY; }
-            pv[e] = __builtin_amdgcn_exp2f(t);
+            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * rq + e], scale_log2, -l4[e]));
             dsv[e] = pv[e] * (dp[4 * rq + e] - d4[e]);
         }
         pp[2 * rq] = pack_bf16(pv[0], pv[1]);  pp[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
         pd[2 * rq] = pack_bf16(dsv[0], dsv[1]); pd[2 * rq + 1] = pack_bf16(dsv[2], dsv[3]);
-    }
+    };
+    quad(0);
+    quad(1);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-        u32x4 a = {pp[4 * b2], pp[4 * b2 + 1], pp[4 * b2 + 2], pp[4 * b2 + 3]};
-        u32x4 b = {pd[4 * b2], pd[4 * b2 + 1], pd[4 * b2 + 2], pd[4 * b2 + 3]};
-        const bf16x8 pfr = as_bf16x8(a), dsfr = as_bf16x8(b);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            acc_dv[db] = mfma32(frag_col(dOt, fa, 2 * ib + b2, db), pfr, acc_dv[db]);
-            acc_dk[db] = mfma32(frag_col(Qt, fa, 2 * ib + b2, db), dsfr, acc_dk[db]);
+    for (int i = 0; i < 16; ++i) {            // i = 8*b2 + 4*which + db
+        const int b2 = i >> 3, which = (i >> 2) & 1, db = i & 3;
+        u32x4 bv = which ? u32x4{pd[4 * b2], pd[4 * b2 + 1], pd[4 * b2 + 2], pd[4 * b2 + 3]}
+                         : u32x4{pp[4 * b2], pp[4 * b2 + 1], pp[4 * b2 + 2], pp[4 * b2 + 3]};
+        if (which) acc_dk[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc_dk[db]);
+        else acc_dv[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc_dv[db]);
+        if (i + kCAhead < 16) {
+            const int n = i + kCAhead;
+            cf[i % kCAhead] = frag_col(((n >> 2) & 1) ? Qt : dOt, fa, 2 * ib + (n >> 3), n & 3);
         }
+        if (i == 1) quad(2);                  // the second contraction step's rows, under the first's MFMAs
+        if (i == 4) quad(3);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-__global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
+__global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* slot = reinterpret_cast<int*>(smem + 2 * kKvStage);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int* slot = reinterpret_cast<int*>(smem + kKvStages * kKvStageBytes);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const uint32_t q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
 
     FragAddr fa;
     fa.init(lane);
-    TileMover<kKvBM, kKvThreads> mq, mdo;
-    mq.init(tid, (uint32_t)q_stride * 2);
-    mdo.init(tid, (uint32_t)q_stride * 2);
-    const uint32_t tile_bytes = kKvBM * (uint32_t)q_stride * 2;       // one Q/dO tile in global memory
-    // a negative scale flips the sign bits of the K fragments, which only the score product reads
-    const float scale_log2 = fabsf(p.scale_log2);
+    const int dma_row = 4 * wave + (lane >> 4);
+    const uint32_t dma_voff = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t tile_bytes = kKvBM * q_stride_b;                   // one Q/dO tile in global memory
+    // a negative scale flips the sign bits of the K fragments, which only the score product reads;
+    // a zero scale becomes an epsilon so that -inf * scale = -inf
+    const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
 
     WorkFetcher wf;
@@ -345,10 +378,39 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
         const int wkey0 = j0 + 32 * wave;                     // first key of this wave
         const int key = wkey0 + l32;
         const bool kvalid = key < L;
+        const bool active = wkey0 < L;
         const int qt_first = j0 / kKvBM;                      // first query tile that sees key j0
         const int n_qt = (L + kKvBM - 1) / kKvBM - qt_first;
         const int n_iter = n_qt * G;
-        const uint32_t q_bytes = (uint32_t)(L - 1) * (uint32_t)q_stride * 2 + kRowBytes;
+        const uint32_t q_bytes = (uint32_t)(L - 1) * q_stride_b + kRowBytes;
+        const uint32_t stat_bytes = (uint32_t)L * 4;
+
+        // stage load of iteration `it` = (query head it / n_qt of the group, query tile it % n_qt)
+        auto dma_stage = [&](int it, int stage) {
+            const int h = g * G + it / n_qt;
+            const int qt = qt_first + it % n_qt;
+            const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * kHeadDim;
+            const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + base, q_bytes);
+            const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.d_o + base, q_bytes);
+            char* dst = smem + stage * kKvStageBytes + 4 * wave * kRowBytes;
+#pragma unroll
+            for (int j = 0; j < 16 / kKvWaves; ++j) {
+                const uint32_t soff = (uint32_t)qt * tile_bytes + (uint32_t)(j * kKvWaves * 4) * q_stride_b;
+                char* d = dst + j * kKvWaves * 4 * kRowBytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, (lds_void_b*)d, 16, dma_voff, soff, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rdo, (lds_void_b*)(d + kKvTileBytes), 16, dma_voff, soff, 0, 0);
+            }
+            // LSE2 and D of the tile's 64 rows: one 256-byte load each (waves 0 and 1); rows past
+            // the sequence read as 0, which is harmless because their Q and dO rows are 0 too
+            if (wave < 2) {
+                const float* src = (wave == 0 ? p.lse2 : p.D) + (int64_t)h * p.T + row0;
+                const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, stat_bytes);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + wave * kKvBM * 4),
+                                                         4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
+            }
+        };
+        dma_stage(0, 0);
+        if (n_iter > 1) dma_stage(1, 1);
 
         bf16x8 kf[8], vf[8];
         {
@@ -369,58 +431,33 @@ __global__ void __launch_bounds__(kKvThreads) hyd_bwd_dkdv_bf16_kernel(BwdParams
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc_dk[db][r] = 0.f; acc_dv[db][r] = 0.f; }
+        __syncthreads();                                      // stages 0 and 1 have landed
 
-        float stat = 0.f;                                     // threads 0..63: lse2, 64..127: D
-        auto stage_load = [&](int it) {
-            const int h = g * G + it / n_qt;
-            const int qt0 = (qt_first + it % n_qt) * kKvBM;
-            const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * kHeadDim;
-            mq.load(make_rsrc(p.q + base, q_bytes), (uint32_t)(qt0 / kKvBM) * tile_bytes);
-            mdo.load(make_rsrc(p.d_o + base, q_bytes), (uint32_t)(qt0 / kKvBM) * tile_bytes);
-            if (tid < 2 * kKvBM) {
-                const int i = qt0 + (tid & (kKvBM - 1));
-                const bool is_lse = tid < kKvBM;
-                stat = is_lse ? INFINITY : 0.f;               // rows past the end: P = exp2(-inf) = 0
-                if (i < L) {
-                    const int64_t at = (int64_t)h * p.T + row0 + i;
-                    stat = is_lse ? p.lse2[at] : p.D[at];
-                }
-            }
-        };
-        auto stage_store = [&](char* base) {
-            mq.store(base);
-            mdo.store(base + kKvTileBytes);
-            if (tid < 2 * kKvBM) reinterpret_cast<float*>(base + 2 * kKvTileBytes)[tid] = stat;
-        };
-        stage_load(0);
-        stage_store(smem);
-        __syncthreads();
-        auto step = [&](auto buf_tag, int it) {
-            constexpr int BUF = decltype(buf_tag)::value;
-            const char* base = smem + BUF * kKvStage;
+        auto step = [&](auto stage_tag, int it) {
+            constexpr int ST = decltype(stage_tag)::value;
+            constexpr int ST2 = (ST + 2) % kKvStages;
+            const char* base = smem + ST * kKvStageBytes;
             const char* Qt = base;
             const char* dOt = base + kKvTileBytes;
             const float* lse2_t = reinterpret_cast<const float*>(base + 2 * kKvTileBytes);
             const float* D_t = lse2_t + kKvBM;
-            const bool more = it + 1 < n_iter;
-            if (more) stage_load(it + 1);
+            if (it + 2 < n_iter) dma_stage(it + 2, ST2);
             const int qt0 = (qt_first + it % n_qt) * kKvBM;
+            if (active) {
 #pragma unroll
-            for (int ib = 0; ib < 2; ++ib) {
-                const int ifirst = qt0 + 32 * ib;             // first query row of the block
-                if (ifirst + 31 >= wkey0) {                   // some row sees some key of the wave
-                    if (ifirst < wkey0 + 31)
-                        dkdv_block<true>(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2, qt0, key, half);
-                    else
-                        dkdv_block<false>(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2, qt0, key, half);
+                for (int ib = 0; ib < 2; ++ib) {
+                    const int ifirst = qt0 + 32 * ib;         // first query row of the block
+                    if (ifirst + 31 >= wkey0)                 // some row sees some key of the wave
+                        dkdv_block(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2,
+                                   ifirst < wkey0 + 31, key - ifirst, half);
                 }
             }
-            if (more) stage_store(smem + (BUF ^ 1) * kKvStage);
             __syncthreads();
         };
-        for (int it = 0; it < n_iter; it += 2) {
+        for (int it = 0; it < n_iter; it += 3) {
             step(std::integral_constant<int, 0>{}, it);
             if (it + 1 < n_iter) step(std::integral_constant<int, 1>{}, it + 1);
+            if (it + 2 < n_iter) step(std::integral_constant<int, 2>{}, it + 2);
         }
         if (kvalid) {
             const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim;
