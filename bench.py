@@ -60,6 +60,11 @@ def run_gpu(cid, steps, warmup):
         for name, ms in tf + tb:
             per_kernel.setdefault(name, []).append(ms)
 
+    # one plain copy kernel of known size (256 MiB read, 256 MiB written), outside the timed
+    # region: the reference that scales the HBM counters of a `rocprofv3 --pmc` run of this command
+    cal = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    torch.add(cal, 0.0, out=torch.empty_like(cal))
+    del cal
     for _ in range(warmup):
         step(False)
     torch.cuda.synchronize()
@@ -79,33 +84,51 @@ def run_gpu(cid, steps, warmup):
 
 
 def cpu_baseline(cid):
-    """The fp64 oracle, as it stands, on a bounded sample of the workload: the sequences of the
-    configuration no longer than 2048 tokens, all heads, forward + backward."""
-    import numpy as np
+    """The fp64 oracle, as it stands, on a bounded sample of the workload (about 2-3e12 flop,
+    10-30 s on 16 cores): as many KV groups as the oracle has threads (its OpenMP loop runs over
+    (sequence, KV group) units), and the sequences of the configuration from the shortest up
+    until the budget is spent; forward + backward."""
     from oracle import attn_oracle as orc
     from paper_2412_07894_amd import workloads as wl
     cfg = wl.CONFIGS[cid]
     lengths = wl.seqlens(cid)
-    keep = [L for L in lengths if L <= 2048]
-    budget_pairs = 1.7e8 / cfg.hq             # about 3e11 flop: 10-30 s of CPU work
-    sample, acc = [], 0
-    for L in sorted(keep, reverse=True):
-        if acc + L * (L + 1) // 2 > budget_pairs and sample:
-            continue
+    G = cfg.hq // cfg.hkv
+    groups = int(max(1, min(cfg.hkv, orc.threads())))
+    budget = 3.0e12 / groups
+    sample, spent = [], 0.0
+    for L in sorted(lengths):
+        cost = 14.0 * cfg.d * G * (L * (L + 1) // 2)
+        if sample and spent + cost > budget:
+            break
         sample.append(L)
-        acc += L * (L + 1) // 2
-    cu, q, k, v, do = wl.custom(sample, cfg.hq, cfg.hkv, cfg.d, cfg.dtype, seed=77)
+        spent += cost
+    per_group = 14.0 * cfg.d * G * wl.causal_pairs(sample)
+    cu, q, k, v, do = wl.custom(sample, groups * G, groups, cfg.d, cfg.dtype, seed=77)
     t0 = time.perf_counter()
     orc.fwd(q, k, v, cu, cfg.scale)
     orc.bwd(q, k, v, do, cu, cfg.scale)
     dt = time.perf_counter() - t0
-    flops = 14.0 * cfg.d * cfg.hq * wl.causal_pairs(sample)
+    flops = per_group * groups
     return {
-        "value": flops / dt / 1e12, "unit": "useful TFLOP/s", "cores": orc.threads(), "kind": "oracle",
-        "sample": f"fp64 oracle fwd+bwd on {len(sample)} of the {len(lengths)} sequences of config {cid} "
-                  f"(those <= 2048 tokens, {int(sum(sample))} of {cfg.total_tokens} tokens), all {cfg.hq} heads, "
-                  f"{dt:.1f} s",
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.threads(), "kind": "oracle",
+        "sample": f"fp64 oracle fwd+bwd on the {len(sample)} shortest of the {len(lengths)} sequences of config {cid} "
+                  f"({int(sum(sample))} of {cfg.total_tokens} tokens, longest {max(sample)}), {groups * G} of {cfg.hq} "
+                  f"query heads ({groups} KV groups), {flops / 1e12:.2f} useful TFLOP in {dt:.1f} s",
     }
+
+
+def measured_traffic(cid, kernel):
+    """Scaled HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_summary.txt), or None when no counter run covers this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_summary.txt")
+    try:
+        for line in open(path):
+            parts = [x.strip() for x in line.split("|")]
+            if len(parts) == 3 and parts[0] == f"config {cid}" and parts[1] == kernel:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -141,7 +164,7 @@ def main():
         ach = alg / (kernels[dom] * 1e-3) / 1e12
         peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3
         out["roofline"] = {"kernel": dom, "bound": "mfma" if cfg.dtype == "bf16" else "alu", "achieved": ach,
-                           "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                           "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": measured_traffic(cfg.cid, dom),
                            "avg_ms": kernels[dom]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)

@@ -18,6 +18,8 @@
  *     [T][Hkv][d]; LSE is float [Hq][T] (natural log).  dtype HYD_BF16: 2-byte bfloat16 elements,
  *     head_dim 128; dtype HYD_FP32: 4-byte float elements, head_dim 64 or 128.  Outputs have the
  *     dtype of the inputs and are fully overwritten.
+ *   - Tiles are fetched through 32-bit buffer resources based at the start of a sequence, so
+ *     max_seqlen * Hq * head_dim * element size must be below 4 GiB (HYD_ERR_SHAPE otherwise).
  *   - cu_seqlens is int32[num_seqs+1] ON THE DEVICE: cu[0] = 0, cu[num_seqs] = T, non-decreasing;
  *     sequence s owns packed rows [cu[s], cu[s+1]).  Empty sequences are legal.  Every token
  *     belongs to exactly one sequence.  `cu_seqlens_host` is an optional HOST copy of the same
@@ -43,7 +45,7 @@ extern "C" {
 typedef enum {
     HYD_OK = 0,
     HYD_ERR_NULL = 1,       /* a required pointer is NULL */
-    HYD_ERR_SHAPE = 2,      /* negative sizes, max_seqlen smaller than the longest sequence */
+    HYD_ERR_SHAPE = 2,      /* negative sizes, max_seqlen out of range or below the longest sequence */
     HYD_ERR_DTYPE = 3,      /* dtype is neither HYD_BF16 nor HYD_FP32 */
     HYD_ERR_HEADS = 4,      /* hq <= 0, hkv <= 0 or hq % hkv != 0 */
     HYD_ERR_HEADDIM = 5,    /* head_dim not supported for this dtype */
@@ -133,7 +135,8 @@ int  hyd_kernel_times(const char** names, float* ms, int cap);
  * fwd / bwd calls on this host thread writes one record of 4 x uint64:
  *     { kernel id (0 fwd, 1 dK/dV, 2 dQ) << 32 | physical CU key (XCC id, SE id, CU id),
  *       start clock, end clock, number of work items processed }
- * at index (kernel id * grid + workgroup).  Pass NULL to switch it off.  The clock is the
+ * at index (kernel id * (capacity_records / 3) + workgroup); workgroups beyond capacity_records / 3
+ * write nothing.  Pass NULL to switch it off.  The clock is the
  * constant-rate wall clock (100 MHz).  For measurement builds only: adds two clock reads and one
  * 32-byte store per workgroup.
  */

@@ -83,6 +83,10 @@ hyd_status validate_common(const int32_t* cu, int num_seqs, const int32_t* cu_ho
     if (T == 0 || num_seqs == 0) return HYD_OK;
     if (!cu) return HYD_ERR_NULL;
     if (max_seqlen > T || max_seqlen < 1) return HYD_ERR_SHAPE;
+    // a sequence must fit the 32-bit range of a buffer resource based at its first row
+    if ((unsigned long long)max_seqlen * (unsigned long long)hq * (unsigned long long)head_dim *
+            (dt == HYD_BF16 ? 2ull : 4ull) >= (1ull << 32))
+        return HYD_ERR_SHAPE;
     if (cu_host) {
         if (cu_host[0] != 0 || cu_host[num_seqs] != T) return HYD_ERR_SEQLENS;
         int longest = 0;

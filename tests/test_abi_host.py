@@ -72,6 +72,7 @@ def test_forward_argument_errors(lib):
     assert call_fwd(lib, cu=None) == NULL
     assert call_fwd(lib, max_len=0) == SHAPE
     assert call_fwd(lib, max_len=257) == SHAPE
+    assert call_fwd(lib, T=1 << 20, max_len=1 << 20, hq=32, hkv=32) == SHAPE     # 2^20 * 32 * 128 * 2 = 2^33 bytes
     keep, p = host_cu([0, 100, 250]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # does not end at T
     keep, p = host_cu([1, 100, 256]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # does not start at 0
     keep, p = host_cu([0, 260, 256]);  assert call_fwd(lib, cu_host=p) == SEQLENS     # decreasing
