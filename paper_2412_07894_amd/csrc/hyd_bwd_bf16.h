@@ -258,98 +258,37 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
 }
 
 // ---------------------------------------------------------------------------------------------
-// dK/dV.  Work item = (sequence, 128-key tile, KV head); wave w owns keys 32w..32w+31 and keeps
-// their K and V rows in registers as B fragments.  Query tiles of 64 rows (Q, dO, LSE2, D) stream
-// through a ring of LDS stages by direct-to-LDS loads, for every query head of the KV group in
-// turn, accumulating into the same dK/dV registers.  S[i][j] = Q K^T and dP[i][j] = dO V^T put
-// one KEY in each lane (column) and query rows in the accumulator slots, so P and dS are directly
-// the B fragments (contraction index = query row) of dV^T[d][j] = dO^T P and dK^T[d][j] = Q^T dS,
-// whose A fragments come from the transposing LDS read of the same dO and Q tiles.
+// dK/dV.  Work item = (sequence, 128-key tile, KV head).  A workgroup has 8 waves in 4 pairs; pair
+// p owns keys 32p..32p+31 of the tile.  The two waves of a pair share a SIMD and split the four
+// products of a (32 query rows x 32 keys) block by role, so that each wave needs half the
+// accumulators (two waves fit one SIMD) and each hides the other's non-MFMA work:
+//     role A (waves 0-3): S = Q K^T  -> P = exp2(S*scale - LSE2) -> hands P to its partner through
+//                         LDS -> dV^T += dO^T P
+//     role B (waves 4-7): dP = dO V^T -> takes P -> dS = P (dP - D) -> dK^T += Q^T dS
+// S[i][j] and dP[i][j] put one KEY in each lane (accumulator column) and query rows in the slots,
+// so P and dS are directly the B fragments (contraction index = query row) of the second
+// products, whose A fragments come from the transposing LDS read of the dO and Q tiles.  P crosses
+// lane-to-lane in fp32 (same accumulator layout on both sides).
+// Query tiles of 64 rows (Q, dO, LSE2, D) stream through a ring of 3 LDS stages by
+// direct-to-LDS loads, for every query head of the KV group in turn, accumulating into the same
+// registers.  One workgroup barrier per 32-row block: it publishes P and, every second block,
+// the next tile.
 // ---------------------------------------------------------------------------------------------
-constexpr int kKvWaves = 4;
-constexpr int kKvBN = 32 * kKvWaves, kKvBM = 64, kKvThreads = 64 * kKvWaves, kKvStages = 3;
+constexpr int kKvPairs = 4, kKvWaves = 2 * kKvPairs;
+constexpr int kKvBN = 32 * kKvPairs, kKvBM = 64, kKvThreads = 64 * kKvWaves, kKvStages = 3;
 constexpr int kKvTileBytes = kKvBM * kRowBytes;                       // 16 KB
 constexpr int kKvStageBytes = 2 * kKvTileBytes + 2 * kKvBM * 4;       // Q, dO, LSE2, D
-constexpr int kKvLds = kKvStages * kKvStageBytes + 64;
-
-// One 32-row query block (rows 32*ib.. of the staged tile) against the 32 keys of a wave.
-// `mask`: the block straddles the diagonal (key > query row is hidden); irel = key - first row.
-__device__ __forceinline__ void dkdv_block(const char* Qt, const char* dOt, const float* lse2_t,
-                                           const float* D_t, const FragAddr& fa, int ib,
-                                           const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
-                                           f32x16 (&acc_dk)[4], f32x16 (&acc_dv)[4], float scale_log2,
-                                           bool mask, int irel, int half) {
-    // instruction order pinned with scheduling fences (see the forward kernel)
-    f32x16 s, dp;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-    {
-        // fragment i < 8: Q, contraction step i; i >= 8: dO, step i - 8; reads run kAhead ahead
-        constexpr int kAhead = 6;
-        bf16x8 f[kAhead];
-#pragma unroll
-        for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < 8 ? Qt : dOt, fa, ib, i & 7);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if (i < 8) s = mfma32(f[i % kAhead], kf[i], s);
-            else dp = mfma32(f[i % kAhead], vf[i - 8], dp);
-            if (i + kAhead < 16) f[i % kAhead] = frag_row(i + kAhead < 8 ? Qt : dOt, fa, ib, (i + kAhead) & 7);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    // A fragments of the two accumulating products: fragment i = (contraction step i/8, product
-    // (i/4)%2: 0 = dV from dO, 1 = dK from Q, head-dim block i%4), requested kCAhead ahead
-    constexpr int kCAhead = 4;
-    bf16x8 cf[kCAhead];
-#pragma unroll
-    for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(((i >> 2) & 1) ? Qt : dOt, fa, 2 * ib + (i >> 3), i & 3);
-    __builtin_amdgcn_sched_barrier(0);
-    if (mask) {                               // hidden pairs: P = exp2(-inf) = 0
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (irel > 8 * (r >> 2) + 4 * half + (r & 3)) s[r] = -INFINITY;
-    }
-    // P and dS for query rows 4*rq + 4*half.. of the block, as packed bf16 pairs
-    uint32_t pp[8], pd[8];
-    auto quad = [&](int rq) {
-        const int i0 = 32 * ib + 8 * rq + 4 * half;           // first of 4 consecutive query rows
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2_t + i0);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(D_t + i0);
-        float pv[4], dsv[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * rq + e], scale_log2, -l4[e]));
-            dsv[e] = pv[e] * (dp[4 * rq + e] - d4[e]);
-        }
-        pp[2 * rq] = pack_bf16(pv[0], pv[1]);  pp[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
-        pd[2 * rq] = pack_bf16(dsv[0], dsv[1]); pd[2 * rq + 1] = pack_bf16(dsv[2], dsv[3]);
-    };
-    quad(0);
-    quad(1);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {            // i = 8*b2 + 4*which + db
-        const int b2 = i >> 3, which = (i >> 2) & 1, db = i & 3;
-        u32x4 bv = which ? u32x4{pd[4 * b2], pd[4 * b2 + 1], pd[4 * b2 + 2], pd[4 * b2 + 3]}
-                         : u32x4{pp[4 * b2], pp[4 * b2 + 1], pp[4 * b2 + 2], pp[4 * b2 + 3]};
-        if (which) acc_dk[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc_dk[db]);
-        else acc_dv[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc_dv[db]);
-        if (i + kCAhead < 16) {
-            const int n = i + kCAhead;
-            cf[i % kCAhead] = frag_col(((n >> 2) & 1) ? Qt : dOt, fa, 2 * ib + (n >> 3), n & 3);
-        }
-        if (i == 1) quad(2);                  // the second contraction step's rows, under the first's MFMAs
-        if (i == 4) quad(3);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
+constexpr int kKvPBytes = 64 * 16 * 4;                                // one block of P: 64 lanes x 16 floats
+constexpr int kKvPOff = kKvStages * kKvStageBytes;                    // P exchange: [pair][2][kKvPBytes]
+constexpr int kKvLds = kKvPOff + kKvPairs * 2 * kKvPBytes + 64;
 
 __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* slot = reinterpret_cast<int*>(smem + kKvStages * kKvStageBytes);
+    int* slot = reinterpret_cast<int*>(smem + kKvPOff + kKvPairs * 2 * kKvPBytes);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pair = wave & (kKvPairs - 1);
+    const bool role_b = wave >= kKvPairs;
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
@@ -366,6 +305,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     // a zero scale becomes an epsilon so that -inf * scale = -inf
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
+    char* const pbuf = smem + kKvPOff + pair * 2 * kKvPBytes + lane * 16;     // + buf * kKvPBytes + q * 1024
 
     WorkFetcher wf;
     wf.init();
@@ -375,7 +315,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
         const int n_tiles = (L + kKvBN - 1) / kKvBN;
         const int j0 = (n_tiles - lev) * kKvBN;               // first key of the item
-        const int wkey0 = j0 + 32 * wave;                     // first key of this wave
+        const int wkey0 = j0 + 32 * pair;                     // first key of this wave pair
         const int key = wkey0 + l32;
         const bool kvalid = key < L;
         const bool active = wkey0 < L;
@@ -385,7 +325,9 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         const uint32_t q_bytes = (uint32_t)(L - 1) * q_stride_b + kRowBytes;
         const uint32_t stat_bytes = (uint32_t)L * 4;
 
-        // stage load of iteration `it` = (query head it / n_qt of the group, query tile it % n_qt)
+        // stage load of iteration `it` = (query head it / n_qt of the group, query tile it % n_qt);
+        // every wave issues exactly kDmaPerStage loads, so that a vmcnt wait can tell stages apart
+        constexpr int kDmaPerStage = 2 * (16 / kKvWaves) + 1;
         auto dma_stage = [&](int it, int stage) {
             const int h = g * G + it / n_qt;
             const int qt = qt_first + it % n_qt;
@@ -400,59 +342,123 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, (lds_void_b*)d, 16, dma_voff, soff, 0, 0);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rdo, (lds_void_b*)(d + kKvTileBytes), 16, dma_voff, soff, 0, 0);
             }
-            // LSE2 and D of the tile's 64 rows: one 256-byte load each (waves 0 and 1); rows past
-            // the sequence read as 0, which is harmless because their Q and dO rows are 0 too
-            if (wave < 2) {
-                const float* src = (wave == 0 ? p.lse2 : p.D) + (int64_t)h * p.T + row0;
-                const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, stat_bytes);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + wave * kKvBM * 4),
-                                                         4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
-            }
+            // LSE2 and D of the tile's 64 rows: one 256-byte load each, by waves 0 and 1 (the other
+            // waves repeat wave 1's load so that all waves count alike); rows past the sequence
+            // read as 0, which is harmless because their Q and dO rows are 0 too
+            const int which = wave == 0 ? 0 : 1;
+            const float* src = (which == 0 ? p.lse2 : p.D) + (int64_t)h * p.T + row0;
+            const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, stat_bytes);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + which * kKvBM * 4),
+                                                     4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
         };
         dma_stage(0, 0);
         if (n_iter > 1) dma_stage(1, 1);
 
-        bf16x8 kf[8], vf[8];
+        // this wave's register operand of the first product: K rows (role A) or V rows (role B)
+        bf16x8 bf[8];
         {
+            const uint16_t* src = role_b ? p.v : p.k;
+            const uint32_t flip = role_b ? 0u : sign_flip;
             const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim + 8 * half;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-                if (kvalid) {
-                    a = *reinterpret_cast<const u32x4*>(p.k + off + 16 * ks);
-                    b = *reinterpret_cast<const u32x4*>(p.v + off + 16 * ks);
-                }
-                kf[ks] = as_bf16x8(a ^ sign_flip);
-                vf[ks] = as_bf16x8(b);
+                u32x4 a = {0u, 0u, 0u, 0u};
+                if (kvalid) a = *reinterpret_cast<const u32x4*>(src + off + 16 * ks);
+                bf[ks] = as_bf16x8(a ^ flip);
             }
         }
-        f32x16 acc_dk[4], acc_dv[4];
+        f32x16 acc[4];                                        // dV^T (role A) or dK^T (role B)
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { acc_dk[db][r] = 0.f; acc_dv[db][r] = 0.f; }
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
         __syncthreads();                                      // stages 0 and 1 have landed
 
+        // one 32-row block: rows 32*ib.. of the tile in `base`; `parity` selects the P buffer
+        auto block = [&](const char* base, int ib, int parity, int qt0) {
+            const char* T1 = base + (role_b ? kKvTileBytes : 0);          // first product reads Q (A) / dO (B)
+            const char* T2 = base + (role_b ? 0 : kKvTileBytes);          // second product reads dO (A) / Q (B)
+            const float* stat = reinterpret_cast<const float*>(base + 2 * kKvTileBytes) + (role_b ? kKvBM : 0);
+            const int ifirst = qt0 + 32 * ib;                 // first query row of the block
+            const bool work = active && ifirst + 31 >= wkey0; // some row sees some key of the pair
+            f32x16 x;
+            uint32_t pk[8];
+            if (work) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[r] = 0.f;
+                constexpr int kAhead = 6;
+                bf16x8 f[kAhead];
+#pragma unroll
+                for (int i = 0; i < kAhead; ++i) f[i] = frag_row(T1, fa, ib, i);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    x = mfma32(f[i % kAhead], bf[i], x);
+                    if (i + kAhead < 8) f[i % kAhead] = frag_row(T1, fa, ib, i + kAhead);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (!role_b) {
+                    if (ifirst < wkey0 + 31) {                // the block straddles the diagonal
+                        const int irel = key - ifirst;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (irel > 8 * (r >> 2) + 4 * half + (r & 3)) x[r] = -INFINITY;
+                    }
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
+                        f32x4 pv;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, -l4[e]));
+                        *reinterpret_cast<f32x4*>(pbuf + parity * kKvPBytes + rq * 1024) = pv;
+                        pk[2 * rq] = pack_bf16(pv[0], pv[1]);
+                        pk[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
+                    }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): P is in LDS
+            __builtin_amdgcn_s_barrier();
+            if (work) {
+                if (role_b) {
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
+                        const f32x4 pv = *reinterpret_cast<const f32x4*>(pbuf + parity * kKvPBytes + rq * 1024);
+                        pk[2 * rq] = pack_bf16(pv[0] * (x[4 * rq] - d4[0]), pv[1] * (x[4 * rq + 1] - d4[1]));
+                        pk[2 * rq + 1] = pack_bf16(pv[2] * (x[4 * rq + 2] - d4[2]), pv[3] * (x[4 * rq + 3] - d4[3]));
+                    }
+                }
+                constexpr int kCAhead = 4;
+                bf16x8 cf[kCAhead];
+#pragma unroll
+                for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(T2, fa, 2 * ib + (i >> 2), i & 3);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {                 // i = 4*b2 + db
+                    const int b2 = i >> 2, db = i & 3;
+                    u32x4 bv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
+                    acc[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc[db]);
+                    if (i + kCAhead < 8) cf[i % kCAhead] = frag_col(T2, fa, 2 * ib + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
         auto step = [&](auto stage_tag, int it) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int ST2 = (ST + 2) % kKvStages;
             const char* base = smem + ST * kKvStageBytes;
-            const char* Qt = base;
-            const char* dOt = base + kKvTileBytes;
-            const float* lse2_t = reinterpret_cast<const float*>(base + 2 * kKvTileBytes);
-            const float* D_t = lse2_t + kKvBM;
-            if (it + 2 < n_iter) dma_stage(it + 2, ST2);
+            const bool more2 = it + 2 < n_iter;
             const int qt0 = (qt_first + it % n_qt) * kKvBM;
-            if (active) {
-#pragma unroll
-                for (int ib = 0; ib < 2; ++ib) {
-                    const int ifirst = qt0 + 32 * ib;         // first query row of the block
-                    if (ifirst + 31 >= wkey0)                 // some row sees some key of the wave
-                        dkdv_block(Qt, dOt, lse2_t, D_t, fa, ib, kf, vf, acc_dk, acc_dv, scale_log2,
-                                   ifirst < wkey0 + 31, key - ifirst, half);
-                }
-            }
-            __syncthreads();
+            block(base, 0, 0, qt0);
+            // every wave has passed this step's first barrier, hence finished the previous step:
+            // the stage that held it may be overwritten now
+            if (more2) dma_stage(it + 2, ST2);
+            // the barrier of the second block also opens the next stage: its loads were issued one
+            // step ago and precede this step's loads in the (in-order) vmcnt queue
+            if (more2) __builtin_amdgcn_s_waitcnt(0x0F70 | (kDmaPerStage & 15) | ((kDmaPerStage >> 4) << 14));
+            else __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+            block(base, 1, 1, qt0);
         };
         for (int it = 0; it < n_iter; it += 3) {
             step(std::integral_constant<int, 0>{}, it);
@@ -461,8 +467,8 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         }
         if (kvalid) {
             const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim;
-            store_rows_bf16(p.dk + off, acc_dk, p.scale, half);
-            store_rows_bf16(p.dv + off, acc_dv, 1.f, half);
+            if (role_b) store_rows_bf16(p.dk + off, acc, p.scale, half);
+            else store_rows_bf16(p.dv + off, acc, 1.f, half);
         }
     }
     trace_write(p.tr, 1, t_start, n_done);

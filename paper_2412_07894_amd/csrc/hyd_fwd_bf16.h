@@ -76,7 +76,9 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             s[i & 1] = mfma32(kf[i % kAhead], qf[i >> 1], s[i & 1]);
+#ifndef HYD_ABL_NOLDS
             if (i + kAhead < 16) kf[i % kAhead] = frag_row(Kt, fa, (i + kAhead) & 1, (i + kAhead) >> 1);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -118,9 +120,13 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
     float lsum = 0.f;
     auto exp_pair = [&](int j) -> uint32_t {           // scores 2j, 2j+1 of the 32 a lane holds
         const int kb = j >> 3, r = (2 * j) & 15;
+#ifdef HYD_ABL_NOEXP
+        const float p0 = s[kb][r], p1 = s[kb][r + 1];
+#else
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2, -m_ref));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r + 1], scale_log2, -m_ref));
         lsum += p0 + p1;
+#endif
         return pack_bf16(p0, p1);
     };
     u32x4 pcur, pnxt;
@@ -131,7 +137,9 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
     for (int i = 0; i < 16; ++i) {                      // i = 4*b + db
         const int b = i >> 2, db = i & 3;
         acc_o[db] = mfma32(vf[i % kVAhead], as_bf16x8(pcur), acc_o[db]);
+#ifndef HYD_ABL_NOLDS
         if (i + kVAhead < 16) vf[i % kVAhead] = frag_col(Vt, fa, (i + kVAhead) >> 2, (i + kVAhead) & 3);
+#endif
         if (b < 3) pnxt[db] = exp_pair(4 * (b + 1) + db);
         __builtin_amdgcn_sched_barrier(0);
         if (db == 3) pcur = pnxt;
@@ -220,9 +228,13 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             constexpr int STN = (ST + 1) % kFwdStages;
             const char* Kt = smem + ST * kFwdStageBytes;
             const char* Vt = Kt + kFwdTileBytes;
+#ifndef HYD_ABL_NODMA
             if (t + 1 < n_kt) dma_tile(t + 1, STN);
+#endif
             if (active && t <= td) fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, krel, t == td, diag_first);
+#ifndef HYD_ABL_NOBAR
             __syncthreads();
+#endif
         };
         if (kFwdStages == 2) {
             for (int t = 0; t < n_kt; t += 2) {
