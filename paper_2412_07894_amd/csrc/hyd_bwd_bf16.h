@@ -92,7 +92,7 @@ typedef __attribute__((address_space(3))) void lds_void_b;
 // One 32-key block (rows 32*kb.. of the K and V tiles) for the 32 rows of a wave.  `k0`: key index
 // minus row index of the block's first key for this lane's row if the block needs masking, else a
 // value that masks nothing.
-__device__ __forceinline__ void dq_block(const char* Kt, const char* Vt, const FragAddr& fa, int kb,
+__device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int kb,
                                          const bf16x8 (&qf)[8], const bf16x8 (&dof)[8], f32x16 (&acc)[4],
                                          float scale_log2, float lse2, float Dq, bool mask, int krel) {
     // instruction order pinned with scheduling fences (see the forward kernel)
@@ -158,7 +158,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
     unsigned long long n_done = 0;
 
     FragAddr fa;
-    fa.init(lane);
+    fa.init(lane, smem);
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
     const uint32_t tile_bytes = kDqBN * kv_stride_b;
@@ -228,8 +228,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
         auto step = [&](auto stage_tag, int t) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int STN = (ST + 1) % kDqStages;
-            const char* Kt = smem + ST * kDqStageBytes;
-            const char* Vt = Kt + kDqTileBytes;
+            constexpr int Kt = ST * kDqStageBytes, Vt = Kt + kDqTileBytes;        // LDS offsets of the tiles
             if (t + 1 < n_kt) dma_tile(t + 1, STN);
             if (active && t <= td) {
                 const bool diag = t == td;
@@ -297,7 +296,12 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     unsigned long long n_done = 0;
 
     FragAddr fa;
-    fa.init(lane);
+    fa.init(lane, smem);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        fa.row[i] += role_b ? kKvTileBytes : 0;
+        fa.col[i] += role_b ? 0 : kKvTileBytes;
+    }
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t dma_voff = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
     const uint32_t tile_bytes = kKvBM * q_stride_b;                   // one Q/dO tile in global memory
@@ -375,10 +379,11 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         __syncthreads();                                      // stages 0 and 1 have landed
 
         // one 32-row block: rows 32*ib.. of the tile in `base`; `parity` selects the P buffer
-        auto block = [&](const char* base, int ib, int parity, int qt0) {
-            const char* T1 = base + (role_b ? kKvTileBytes : 0);          // first product reads Q (A) / dO (B)
-            const char* T2 = base + (role_b ? 0 : kKvTileBytes);          // second product reads dO (A) / Q (B)
-            const float* stat = reinterpret_cast<const float*>(base + 2 * kKvTileBytes) + (role_b ? kKvBM : 0);
+        auto block = [&](int base, int ib, int parity, int qt0) {         // base: LDS offset of the stage
+            // the role's choice of tile (first product reads Q (A) / dO (B), second product reads
+            // dO (A) / Q (B)) is folded into fa.row / fa.col once per kernel
+            const int T1 = base, T2 = base;
+            const float* stat = reinterpret_cast<const float*>(smem + base + 2 * kKvTileBytes) + (role_b ? kKvBM : 0);
             const int ifirst = qt0 + 32 * ib;                 // first query row of the block
             const bool work = active && ifirst + 31 >= wkey0; // some row sees some key of the pair
             f32x16 x;
@@ -447,7 +452,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         auto step = [&](auto stage_tag, int it) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int ST2 = (ST + 2) % kKvStages;
-            const char* base = smem + ST * kKvStageBytes;
+            constexpr int base = ST * kKvStageBytes;
             const bool more2 = it + 2 < n_iter;
             const int qt0 = (qt_first + it % n_qt) * kKvBM;
             block(base, 0, 0, qt0);

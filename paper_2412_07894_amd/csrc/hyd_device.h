@@ -73,36 +73,42 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // is then one LDS instruction whose address is one of these registers plus a compile-time offset
 // (tile base, 32-row block, 16-row contraction step): swz() is invariant under adding multiples
 // of 16 rows, so blocks and steps move the address by plain multiples of kRowBytes.
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
+
 struct FragAddr {
+    // ABSOLUTE LDS byte addresses (the base of the dynamic LDS block is folded in here, once,
+    // because the compiler cannot fold that link-time constant into instruction offsets)
     uint32_t row[8];      // row fragment of row (lane % 32), contraction step ks = 0..7
     uint32_t col[8];      // [2 * cb + hi]: transposing read of column block cb, row group hi, step 0
-    __device__ __forceinline__ void init(int lane) {
+    __device__ __forceinline__ void init(int lane, const char* lds_base) {
         const int l32 = lane & 31, half = lane >> 5, lane16 = lane & 15;
+        const uint32_t base = (uint32_t)(uintptr_t)(lds_char*)lds_base;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) row[ks] = tile_off(l32, 2 * ks + half);
+        for (int ks = 0; ks < 8; ++ks) row[ks] = base + tile_off(l32, 2 * ks + half);
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
 #pragma unroll
             for (int hi = 0; hi < 2; ++hi) {
                 const int r = 4 * half + 8 * hi + (lane16 >> 2);
                 const int c = 32 * cb + (lane & 16) + ((lane16 & 3) << 2);
-                col[2 * cb + hi] = tile_off(r, c >> 3) + ((c & 4) << 1);
+                col[2 * cb + hi] = base + tile_off(r, c >> 3) + ((c & 4) << 1);
             }
         }
     }
 };
 
 // Row fragment (contraction index = head dimension): elements [16*ks + 8*half, +8) of tile row
-// 32*blk + lane%32.
-__device__ __forceinline__ bf16x8 frag_row(const char* tile, const FragAddr& fa, int blk, int ks) {
-    return as_bf16x8(*reinterpret_cast<const u32x4*>(tile + fa.row[ks] + blk * 32 * kRowBytes));
+// 32*blk + lane%32.  `tile` is the tile's byte offset from the LDS base given to FragAddr::init.
+__device__ __forceinline__ bf16x8 frag_row(int tile, const FragAddr& fa, int blk, int ks) {
+    return as_bf16x8(*(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(tile + blk * 32 * kRowBytes)));
 }
 
 // Column fragment (contraction index = tile row): step b (16 rows), column
 // block cb (32 columns).
-__device__ __forceinline__ bf16x8 frag_col(const char* tile, const FragAddr& fa, int b, int cb) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.col[2 * cb] + b * 16 * kRowBytes));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.col[2 * cb + 1] + b * 16 * kRowBytes));
+__device__ __forceinline__ bf16x8 frag_col(int tile, const FragAddr& fa, int b, int cb) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(fa.col[2 * cb] + (uint32_t)(tile + b * 16 * kRowBytes)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(fa.col[2 * cb + 1] + (uint32_t)(tile + b * 16 * kRowBytes)));
     u32x2 l2, h2;
     __builtin_memcpy(&l2, &lo, 8);
     __builtin_memcpy(&h2, &hi, 8);

@@ -56,7 +56,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 // masked and unmasked tiles make the compiler keep the accumulators twice and copy them at every
 // join); only the masking itself sits in a wave-uniform branch.  `diag`: this is the wave's
 // diagonal tile; `diag_first`: its diagonal block is the tile's first block, the second is hidden.
-__device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const FragAddr& fa, const bf16x8 (&qf)[8],
+__device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, const bf16x8 (&qf)[8],
                                          f32x16 (&acc_o)[4], float& m_ref, float& l_run, float scale_log2,
                                          int krel, bool diag, bool diag_first) {
     // The instruction order below is pinned with scheduling fences: left alone, the compiler sinks
@@ -76,9 +76,7 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             s[i & 1] = mfma32(kf[i % kAhead], qf[i >> 1], s[i & 1]);
-#ifndef HYD_ABL_NOLDS
             if (i + kAhead < 16) kf[i % kAhead] = frag_row(Kt, fa, (i + kAhead) & 1, (i + kAhead) >> 1);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -120,14 +118,15 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
     float lsum = 0.f;
     auto exp_pair = [&](int j) -> uint32_t {           // scores 2j, 2j+1 of the 32 a lane holds
         const int kb = j >> 3, r = (2 * j) & 15;
-#ifdef HYD_ABL_NOEXP
-        const float p0 = s[kb][r], p1 = s[kb][r + 1];
-#else
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2, -m_ref));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r + 1], scale_log2, -m_ref));
-        lsum += p0 + p1;
-#endif
-        return pack_bf16(p0, p1);
+        const uint32_t pair = pack_bf16(p0, p1);
+        // row sum of the ROUNDED probabilities (what the P V product actually uses)
+        bf16x2 pr;
+        __builtin_memcpy(&pr, &pair, 4);
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+        return pair;
     };
     u32x4 pcur, pnxt;
 #pragma unroll
@@ -137,9 +136,7 @@ __device__ __forceinline__ void fwd_tile(const char* Kt, const char* Vt, const F
     for (int i = 0; i < 16; ++i) {                      // i = 4*b + db
         const int b = i >> 2, db = i & 3;
         acc_o[db] = mfma32(vf[i % kVAhead], as_bf16x8(pcur), acc_o[db]);
-#ifndef HYD_ABL_NOLDS
         if (i + kVAhead < 16) vf[i % kVAhead] = frag_col(Vt, fa, (i + kVAhead) >> 2, (i + kVAhead) & 3);
-#endif
         if (b < 3) pnxt[db] = exp_pair(4 * (b + 1) + db);
         __builtin_amdgcn_sched_barrier(0);
         if (db == 3) pcur = pnxt;
@@ -160,7 +157,7 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
     unsigned long long n_done = 0;
 
     FragAddr fa;
-    fa.init(lane);
+    fa.init(lane, smem);
     // direct-to-LDS tile load: instruction j of wave w fills tile rows 4*(j*NW + w) .. +3 (1 KB,
     // lane i -> row i/16, chunk position i%16), so lane i fetches the chunk that swz() puts there
     const int dma_row = 4 * wave + (lane >> 4);
@@ -226,15 +223,10 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         auto step = [&](auto stage_tag, int t) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int STN = (ST + 1) % kFwdStages;
-            const char* Kt = smem + ST * kFwdStageBytes;
-            const char* Vt = Kt + kFwdTileBytes;
-#ifndef HYD_ABL_NODMA
+            constexpr int Kt = ST * kFwdStageBytes, Vt = Kt + kFwdTileBytes;      // LDS offsets of the tiles
             if (t + 1 < n_kt) dma_tile(t + 1, STN);
-#endif
             if (active && t <= td) fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, krel, t == td, diag_first);
-#ifndef HYD_ABL_NOBAR
             __syncthreads();
-#endif
         };
         if (kFwdStages == 2) {
             for (int t = 0; t < n_kt; t += 2) {
