@@ -169,11 +169,12 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
     const int krel = 4 * half - l32;
 
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, head;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, head)) {
+    WorkItem wi;
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    while (have) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+        const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kDqBM;
         const int kv_end = min(L, q0 + kDqBM);
         const int n_kt = (kv_end + kDqBN - 1) / kDqBN;
@@ -198,6 +199,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             }
         };
         dma_tile(0, 0);
+        if (kDqStages == 3 && n_kt > 1) dma_tile(1, 1);
 
         bf16x8 qf[8], dof[8];
         float lse2 = 0.f, Dq = 0.f;
@@ -229,14 +231,22 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int STN = (ST + 1) % kDqStages;
             constexpr int Kt = ST * kDqStageBytes, Vt = Kt + kDqTileBytes;        // LDS offsets of the tiles
-            if (t + 1 < n_kt) dma_tile(t + 1, STN);
+            // with a 3-stage ring the loads run two tiles ahead: tile t+1 was requested one step
+            // ago and precedes this step's loads in the (in-order) vmcnt queue
+            constexpr int ST2 = (ST + 2) % kDqStages;
+            constexpr int kDmaPerTile = 2 * (16 / kDqWaves);
+            const bool more2 = kDqStages == 3 && t + 2 < n_kt;
+            if (kDqStages == 3) { if (more2) dma_tile(t + 2, ST2); }
+            else if (t + 1 < n_kt) dma_tile(t + 1, STN);
             if (active && t <= td) {
                 const bool diag = t == td;
                 dq_block(Kt, Vt, fa, 0, qf, dof, acc, scale_log2, lse2, Dq, diag && diag_kb == 0, krel);
                 if (!(diag && diag_kb == 0))
                     dq_block(Kt, Vt, fa, 1, qf, dof, acc, scale_log2, lse2, Dq, diag, krel);
             }
-            __syncthreads();
+            if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
+            else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
         };
         if (kDqStages == 2) {
             for (int t = 0; t < n_kt; t += 2) {
@@ -252,6 +262,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
         }
         if (qvalid)
             store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
+        have = wf.next(slot, wi);
     }
     trace_write(p.tr, 2, t_start, n_done);
 }
@@ -312,11 +323,12 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     char* const pbuf = smem + kKvPOff + pair * 2 * kKvPBytes + lane * 16;     // + buf * kKvPBytes + q * 1024
 
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, g;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, g)) {
+    WorkItem wi;
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    while (have) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+        const int lev = wi.lev, g = wi.head, row0 = wi.row0, L = wi.len;
         const int n_tiles = (L + kKvBN - 1) / kKvBN;
         const int j0 = (n_tiles - lev) * kKvBN;               // first key of the item
         const int wkey0 = j0 + 32 * pair;                     // first key of this wave pair
@@ -475,6 +487,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             if (role_b) store_rows_bf16(p.dk + off, acc, p.scale, half);
             else store_rows_bf16(p.dv + off, acc, 1.f, half);
         }
+        have = wf.next(slot, wi);
     }
     trace_write(p.tr, 1, t_start, n_done);
 }

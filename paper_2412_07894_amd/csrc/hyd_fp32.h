@@ -33,14 +33,14 @@ __device__ __forceinline__ float dot_row(const float (&a)[D], const float* __res
 
 template <int D>
 __global__ void __launch_bounds__(kF32Tile) hyd_fwd_fp32_kernel(F32Params p) {
-    __shared__ int slot[4];
+    __shared__ int slot[kSlotInts];
     const int tid = threadIdx.x;
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, head;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, head)) {
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+    WorkItem wi;
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+        const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kF32Tile;
         const int i = q0 + tid;
         const bool valid = i < L;
@@ -92,14 +92,14 @@ __global__ void __launch_bounds__(256) hyd_bwd_rowdot_fp32_kernel(const float* _
 
 template <int D>
 __global__ void __launch_bounds__(kF32Tile) hyd_bwd_dq_fp32_kernel(F32Params p) {
-    __shared__ int slot[4];
+    __shared__ int slot[kSlotInts];
     const int tid = threadIdx.x;
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, head;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, head)) {
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+    WorkItem wi;
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+        const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kF32Tile;
         const int i = q0 + tid;
         const bool valid = i < L;
@@ -137,10 +137,10 @@ __global__ void __launch_bounds__(kF32Tile) hyd_bwd_dkdv_fp32_kernel(F32Params p
     const int tid = threadIdx.x;
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, g;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, g)) {
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+    WorkItem wi;
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+        const int lev = wi.lev, g = wi.head, row0 = wi.row0, L = wi.len;
         const int n_tiles = (L + kF32Tile - 1) / kF32Tile;
         const int j0 = (n_tiles - lev) * kF32Tile;
         const int j = j0 + tid;

@@ -170,11 +170,12 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
     const int krel = 4 * half - l32;
 
     WorkFetcher wf;
-    wf.init();
-    int seq, lev, head;
-    while (wf.next(p.hm, p.hdr, p.cursors, p.items, slot, seq, lev, head)) {
+    WorkItem wi;
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    while (have) {
+        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
-        const int row0 = p.cu[seq], L = p.cu[seq + 1] - row0;
+        const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kFwdBM;
         const int kv_end = min(L, q0 + kFwdBM);
         const int n_kt = (kv_end + kFwdBN - 1) / kFwdBN;
@@ -200,6 +201,7 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             }
         };
         dma_tile(0, 0);
+        if (kFwdStages == 3 && n_kt > 1) dma_tile(1, 1);
 
         bf16x8 qf[8];
         {
@@ -224,9 +226,17 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int STN = (ST + 1) % kFwdStages;
             constexpr int Kt = ST * kFwdStageBytes, Vt = Kt + kFwdTileBytes;      // LDS offsets of the tiles
-            if (t + 1 < n_kt) dma_tile(t + 1, STN);
+            // with a 3-stage ring the loads run two tiles ahead: tile t+1 was requested one step
+            // ago and precedes this step's loads in the (in-order) vmcnt queue
+            constexpr int ST2 = (ST + 2) % kFwdStages;
+            constexpr int kDmaPerTile = 2 * (16 / kFwdWaves);
+            const bool more2 = kFwdStages == 3 && t + 2 < n_kt;
+            if (kFwdStages == 3) { if (more2) dma_tile(t + 2, ST2); }
+            else if (t + 1 < n_kt) dma_tile(t + 1, STN);
             if (active && t <= td) fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, krel, t == td, diag_first);
-            __syncthreads();
+            if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
+            else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
         };
         if (kFwdStages == 2) {
             for (int t = 0; t < n_kt; t += 2) {
@@ -258,6 +268,7 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
                 p.lse[(int64_t)head * p.T + row0 + qrow] =
                     (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
         }
+        have = wf.next(slot, wi);
     }
     trace_write(p.tr, 0, t_start, n_done);
 }

@@ -124,39 +124,68 @@ __device__ __forceinline__ void decode_work(const HeadMap& hm, int x, int w, int
 }
 
 // Persistent-workgroup work fetch.  Thread 0 takes the next index of the current queue, moving on
-// to the next queue when one is exhausted; the result is broadcast through LDS.  Returns false
-// when all queues are empty (every workgroup reaches this: the cursors only grow).
+// to the next queue when one is exhausted, resolves it to (sequence, level, head) and to the
+// sequence's first packed row and length, and leaves the result in LDS.  The fetch of item k+1
+// is issued at the START of item k (prefetch), so its chain of dependent global accesses (cursor
+// atomic, item list, cu_seqlens) overlaps item k's tile loop; only wave 0, which owns the rows
+// with the shortest causal span, waits for it.  Every workgroup ends when all queues are empty
+// (the cursors only grow).
+struct WorkItem { int seq, lev, head, row0, len; };
+constexpr int kSlotInts = 16;          // two buffers of 8 ints
+
 struct WorkFetcher {
     int queue;      // current queue
     int tried;      // queues found empty so far
-    __device__ __forceinline__ void init() {
+    int cur;        // slot buffer holding the current item
+    __device__ __forceinline__ void fetch_into(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
+                                               const int* __restrict__ items, const int32_t* __restrict__ cu,
+                                               int* buf) {
+        const int n_items = hdr[0];
+        int item = -1, hd = 0;
+        while (tried < kQueues) {
+            const int size = queue_size(hm, n_items, queue);
+            int w = size > 0 ? atomicAdd(&cursors[queue], 1) : size;
+            if (w < size) { decode_work(hm, queue, w, item, hd); break; }
+            queue = (queue + 1) & (kQueues - 1);
+            ++tried;
+        }
+        buf[0] = item;
+        buf[1] = hd;
+        if (item >= 0) {
+            const int sq = items[2 * item];
+            buf[2] = sq;
+            buf[3] = items[2 * item + 1];
+            const int r0 = cu[sq];
+            buf[4] = r0;
+            buf[5] = cu[sq + 1] - r0;
+        }
+    }
+    __device__ __forceinline__ bool read(const int* buf, WorkItem& w) const {
+        if (buf[0] < 0) return false;
+        w.head = buf[1]; w.seq = buf[2]; w.lev = buf[3]; w.row0 = buf[4]; w.len = buf[5];
+        return true;
+    }
+    // `slot`: kSlotInts ints of LDS.  All threads must call first/next (each contains a barrier).
+    __device__ __forceinline__ bool first(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
+                                          const int* __restrict__ items, const int32_t* __restrict__ cu,
+                                          int* slot, WorkItem& w) {
         queue = (__smid() >> 6) & (kQueues - 1);     // XCC id of this workgroup
         tried = 0;
-    }
-    // `slot`: 4 ints of LDS.  All threads must call this; contains two barriers.
-    __device__ __forceinline__ bool next(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
-                                         const int* __restrict__ items, int* slot, int& seq, int& lev,
-                                         int& head) {
-        __syncthreads();        // previous item's readers of `slot` are done
-        if (threadIdx.x == 0) {
-            const int n_items = hdr[0];
-            int item = -1, hd = 0;
-            while (tried < kQueues) {
-                const int size = queue_size(hm, n_items, queue);
-                int w = size > 0 ? atomicAdd(&cursors[queue], 1) : size;
-                if (w < size) { decode_work(hm, queue, w, item, hd); break; }
-                queue = (queue + 1) & (kQueues - 1);
-                ++tried;
-            }
-            slot[0] = item;
-            slot[1] = hd;
-            if (item >= 0) { slot[2] = items[2 * item]; slot[3] = items[2 * item + 1]; }
-        }
+        cur = 0;
+        if (threadIdx.x == 0) fetch_into(hm, hdr, cursors, items, cu, slot);
         __syncthreads();
-        const int item = slot[0];
-        if (item < 0) return false;
-        head = slot[1]; seq = slot[2]; lev = slot[3];
-        return true;
+        return read(slot, w);
+    }
+    // call right after first()/next() returned true
+    __device__ __forceinline__ void prefetch(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
+                                             const int* __restrict__ items, const int32_t* __restrict__ cu,
+                                             int* slot) {
+        if (threadIdx.x == 0) fetch_into(hm, hdr, cursors, items, cu, slot + 8 * (cur ^ 1));
+    }
+    __device__ __forceinline__ bool next(int* slot, WorkItem& w) {
+        __syncthreads();        // the prefetched item is visible; everybody is done with the LDS tiles
+        cur ^= 1;
+        return read(slot + 8 * cur, w);
     }
 };
 
