@@ -64,8 +64,8 @@ const char* hyd_status_string(hyd_status st);
  * Bytes of device workspace that hyd_varlen_attn_fwd (is_bwd = 0) or hyd_varlen_attn_bwd
  * (is_bwd = 1) needs for these sizes.  The workspace holds the work-item schedule (the list of
  * (sequence, tile) items ordered by decreasing cost, and the queue cursors of the persistent
- * workgroups) and, for the backward, the float vector D[Hq][T] = rowsum(dO * O).  Returns 0 for
- * invalid arguments.  Pure host arithmetic: no HIP call.
+ * workgroups) and, for the backward, two float vectors [Hq][T]: D = rowsum(dO * O) and LSE in
+ * base-2 units.  Returns 0 for invalid arguments.  Pure host arithmetic: no HIP call.
  */
 size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, int hkv,
                                        int head_dim, hyd_dtype dt, int is_bwd);
@@ -141,6 +141,21 @@ int  hyd_kernel_times(const char** names, float* ms, int cap);
  * 32-byte store per workgroup.
  */
 void hyd_set_wg_trace(void* device_records, int capacity_records);
+
+/*
+ * Sustained-rate probe of the bf16 matrix pipe, for putting the roofline fraction of the kernels
+ * above into context: enqueues ONE kernel of `workgroups` workgroups (8 waves each, two per
+ * SIMD) that issues `iters` x 4 v_mfma_f32_32x32x16_bf16 per wave on register operands and does
+ * nothing else.  pattern 0: all operands zero; pattern 1: pseudo-random values of magnitude
+ * around one (the sustained clock of the board depends on how many operand bits toggle).
+ *   device_out   device, float[workgroups * 512], overwritten (keeps the result live)
+ *   flops        host, out: floating-point operations the launch performs
+ * Time it with the kernel timing hook above (name "probe_mfma") or with events on `hip_stream`.
+ * Errors: HYD_ERR_NULL, HYD_ERR_SHAPE (non-positive sizes, unknown pattern), HYD_ERR_ARCH,
+ * HYD_ERR_LAUNCH.
+ */
+hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops,
+                          void* hip_stream);
 
 #ifdef __cplusplus
 }

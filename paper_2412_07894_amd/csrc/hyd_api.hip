@@ -10,6 +10,7 @@
 #include "hyd_bwd_bf16.h"
 #include "hyd_fp32.h"
 #include "hyd_fwd_bf16.h"
+#include "hyd_probe.h"
 
 namespace {
 
@@ -383,6 +384,23 @@ int hyd_kernel_times(const char** names, float* ms, int cap) {
 void hyd_set_wg_trace(void* device_records, int capacity_records) {
     t_trace.rec = static_cast<unsigned long long*>(device_records);
     t_trace.capacity = device_records ? capacity_records : 0;
+}
+
+hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops, void* hip_stream) {
+    if (!device_out || !flops) return HYD_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0 || (pattern != 0 && pattern != 1)) return HYD_ERR_SHAPE;
+    DeviceInfo* dev = nullptr;
+    const hyd_status st_dev = device_info(&dev);
+    if (st_dev != HYD_OK) return st_dev;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    timed_clear();
+    {
+        KernelTimer kt("probe_mfma", st);
+        hipLaunchKernelGGL(hyd_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern);
+    }
+    if (hipGetLastError() != hipSuccess) return HYD_ERR_LAUNCH;
+    *flops = (double)workgroups * (kProbeThreads / 64) * (double)iters * kProbeMfmaPerIter * (2.0 * 32 * 32 * 16);
+    return HYD_OK;
 }
 
 }  // extern "C"
