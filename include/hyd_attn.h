@@ -52,7 +52,8 @@ typedef enum {
     HYD_ERR_SEQLENS = 6,    /* host cu_seqlens does not start at 0, end at T or is decreasing */
     HYD_ERR_WORKSPACE = 7,  /* workspace NULL, misaligned (256 B) or smaller than required */
     HYD_ERR_ARCH = 8,       /* the current device is not gfx950 */
-    HYD_ERR_LAUNCH = 9      /* a HIP launch or query failed */
+    HYD_ERR_LAUNCH = 9,     /* a HIP launch or query failed */
+    HYD_ERR_INFEASIBLE = 10 /* planning calls (hyd_plan.h): the constraints admit no solution */
 } hyd_status;
 
 typedef enum { HYD_BF16 = 0, HYD_FP32 = 1 } hyd_dtype;

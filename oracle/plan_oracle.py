@@ -30,14 +30,17 @@ import math
 import numpy as np
 
 
-def fit_latency(lengths, times):
-    """(a, b, c) of T(l) = a l^2 + b l + c by ordinary least squares (App. C.2)."""
+def fit_latency(lengths, times, weights=None):
+    """(a, b, c) of T(l) = a l^2 + b l + c by least squares (App. C.2): minimises
+    sum_i w_i (T(l_i) - t_i)^2, w_i = 1 when no weights are given."""
     l = np.asarray(lengths, dtype=np.float64)
     t = np.asarray(times, dtype=np.float64)
-    if l.size < 3 or np.unique(l).size < 3:
+    w = np.ones_like(l) if weights is None else np.asarray(weights, dtype=np.float64)
+    if np.unique(l[w > 0]).size < 3:
         raise ValueError("need at least three distinct lengths")
-    design = np.stack([l * l, l, np.ones_like(l)], axis=1)
-    coef, *_ = np.linalg.lstsq(design, t, rcond=None)
+    r = np.sqrt(w)
+    design = np.stack([l * l, l, np.ones_like(l)], axis=1) * r[:, None]
+    coef, *_ = np.linalg.lstsq(design, t * r, rcond=None)
     return tuple(float(x) for x in coef)
 
 

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhyd_attn.so")
-SOURCES = [os.path.join(CSRC, "hyd_api.hip")]
+SOURCES = [os.path.join(CSRC, "hyd_api.hip"), os.path.join(CSRC, "hyd_plan.cpp")]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -23,6 +23,7 @@ def sources_newer_than_lib():
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
     deps.append(os.path.join(os.path.dirname(HERE), "include", "hyd_attn.h"))
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "hyd_plan.h"))
     return any(os.path.getmtime(f) > t for f in deps)
 
 

@@ -206,6 +206,7 @@ const char* hyd_status_string(hyd_status st) {
         case HYD_ERR_WORKSPACE: return "HYD_ERR_WORKSPACE: workspace NULL, misaligned or too small";
         case HYD_ERR_ARCH: return "HYD_ERR_ARCH: device is not gfx950";
         case HYD_ERR_LAUNCH: return "HYD_ERR_LAUNCH: HIP launch or query failed";
+        case HYD_ERR_INFEASIBLE: return "HYD_ERR_INFEASIBLE: the planning constraints admit no solution";
     }
     return "unknown hyd_status";
 }

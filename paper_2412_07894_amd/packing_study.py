@@ -1,0 +1,123 @@
+#!/usr/bin/env python3
+"""Cost-aware packing measured on this library's own kernels (Hydraulis, arXiv 2412.07894,
+Sec. 6.1 and App. C.2, D): fit T(l) = a l^2 + b l + c to the measured forward+backward time of
+sequences inside packed buffers, pack a length draw into micro-batches once the way the paper argues against
+(fill to the maximum length, first fit decreasing) and once by Eq. 1 (minimise the longest
+micro-batch times (PP - 1 + V), V enumerated), then run every micro-batch of both packings on the
+GPU and compare predicted with measured times.  Prints one JSON object.
+
+    python -m paper_2412_07894_amd.packing_study --config 5 --pp 4
+"""
+import argparse
+import json
+import statistics
+import sys
+
+
+def time_lengths(lengths, hq, hkv, d, reps, warmup, seed=0):
+    """Median milliseconds of one forward + backward over one packed buffer holding `lengths`."""
+    import numpy as np
+    import torch
+    from . import binding, workloads as wl
+    cu_np = wl.cu_seqlens(lengths)
+    T, ml = int(cu_np[-1]), int(max(lengths))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+
+    def rnd(h):
+        return torch.randn((T, h, d), device="cuda", dtype=torch.float32, generator=g).to(torch.bfloat16)
+    q, k, v, do = rnd(hq), rnd(hkv), rnd(hkv), rnd(hq)
+    cu = torch.from_numpy(cu_np).cuda()
+    scale = 1.0 / float(np.sqrt(d))
+    ws_f = torch.empty(binding.workspace_bytes(T, len(lengths), hq, hkv, d, binding.HYD_BF16, 0), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.workspace_bytes(T, len(lengths), hq, hkv, d, binding.HYD_BF16, 1), dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty((hq, T), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ms = []
+    for it in range(warmup + reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.varlen_attn_fwd(q, k, v, cu, ml, scale, workspace=ws_f, out=o, lse=lse)
+        binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, scale, workspace=ws_b, dq=dq, dk=dk, dv=dv)
+        e1.record()
+        e1.synchronize()
+        if it >= warmup:
+            ms.append(e0.elapsed_time(e1))
+    return statistics.median(ms)
+
+
+def calibrate(hq, hkv, d, probe_lengths, cap, reps=5, warmup=2):
+    """Profiled (length, ms) points and the model fitted to them (App. C.2).  The time of a
+    sequence of length l is taken inside a packed buffer, as it will run: a buffer of
+    k = cap // l copies is timed and divided by k, so that what is paid once per call (launches,
+    the schedule prelude) is not charged to every sequence."""
+    from . import planner
+    times = []
+    for l in probe_lengths:
+        k = max(1, int(cap) // int(l))
+        times.append(time_lengths([int(l)] * k, hq, hkv, d, reps, warmup, seed=int(l)) / k)
+    # relative errors (weights 1 / t^2): the times span three orders of magnitude
+    model = planner.fit_latency([float(l) for l in probe_lengths], times, [1.0 / (t * t) for t in times])
+    return model, times
+
+
+def util_len(model, max_len, threshold=0.85):
+    """Length from which the per-token cost that packing can amortise (b + c/l, the part of
+    T(l)/l that does not grow with l) is within 1/threshold of its floor b: the reading of
+    App. D's "efficiency reaches a threshold (0.85)" for a model that prices attention only."""
+    a, b, c = model.as_tuple()
+    if b <= 0 or c <= 0:
+        return 1
+    return int(max(1, min(max_len, round(c / (b * (1.0 / threshold - 1.0))))))
+
+
+def study(lengths, hq, hkv, d, max_len, pp, probe_lengths, reps=5, warmup=2, node_limit=2_000_000):
+    from . import planner
+    model, probe_ms = calibrate(hq, hkv, d, probe_lengths, max_len, reps, warmup)
+    # what one call costs before any sequence does: launches and the schedule prelude.  Eq. 1 does
+    # not price it (its T(l) is per sequence); it is added to the predictions below so that they
+    # can be compared with measured micro-batch times.
+    call_ms = time_lengths([64], hq, hkv, d, reps, warmup)
+    ul = util_len(model, max_len)
+    out = {"heads": [hq, hkv], "head_dim": d, "max_len": max_len, "pp": pp, "num_seqs": len(lengths),
+           "tokens": int(sum(lengths)), "model_ms": dict(zip("abc", model.as_tuple())),
+           "probe": {"lengths": [int(l) for l in probe_lengths], "ms": probe_ms,
+                     "fit_rel_err": [abs(planner.latency(model, l) - t) / t for l, t in zip(probe_lengths, probe_ms)]},
+           "call_overhead_ms": call_ms, "util_len": ul, "v_range": list(planner.v_range(lengths, max_len, ul))}
+    v_ffd, a_ffd = planner.pack_ffd(lengths, max_len)
+    obj, v_bal, a_bal, proven = planner.pack(lengths, model, max_len, ul, pp, node_limit)
+    for name, V, assign in (("max_length_ffd", v_ffd, a_ffd), ("balanced_eq1", v_bal, a_bal)):
+        batches = [[int(l) for l, j in zip(lengths, assign) if j == b] for b in range(V)]
+        pred = [call_ms + sum(planner.latency(model, l) for l in mb) for mb in batches]
+        meas = [time_lengths(mb, hq, hkv, d, reps, warmup, seed=17 + b) for b, mb in enumerate(batches)]
+        out[name] = {
+            "V": V, "tokens_per_batch": [sum(mb) for mb in batches], "seqs_per_batch": [len(mb) for mb in batches],
+            "predicted_ms": pred, "measured_ms": meas,
+            "predicted_objective_ms": max(pred) * (pp - 1 + V), "measured_objective_ms": max(meas) * (pp - 1 + V),
+            "measured_sum_ms": sum(meas), "measured_max_over_mean": max(meas) / (sum(meas) / V),
+        }
+    out["balanced_eq1"]["search_finished"] = proven
+    out["measured_objective_ratio_ffd_over_balanced"] = (
+        out["max_length_ffd"]["measured_objective_ms"] / out["balanced_eq1"]["measured_objective_ms"])
+    return out
+
+
+def main():
+    from . import workloads as wl
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
+    ap.add_argument("--pp", type=int, default=4)
+    ap.add_argument("--reps", type=int, default=5)
+    args = ap.parse_args()
+    cfg = wl.CONFIGS[args.config]
+    lengths = [int(l) for l in wl.seqlens(args.config)]
+    probes = [l for l in (256, 512, 1024, 2048, 4096, 8192, 12288, 16384, 24576, 32768, 49152, 65536)
+              if l <= cfg.buffer_tokens]
+    res = study(lengths, cfg.hq, cfg.hkv, cfg.d, cfg.buffer_tokens, args.pp, probes, reps=args.reps)
+    res["workload"] = f"config {cfg.cid}: {cfg.name}"
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    sys.exit(main())

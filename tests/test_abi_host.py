@@ -106,8 +106,8 @@ def test_backward_argument_errors(lib):
 
 def test_status_strings(lib):
     from paper_2412_07894_amd import binding as b
-    seen = {b.status_string(c) for c in range(10)}
-    assert len(seen) == 10 and all(s.startswith("HYD_") for s in seen)
+    seen = {b.status_string(c) for c in range(11)}
+    assert len(seen) == 11 and all(s.startswith("HYD_") for s in seen)
     assert "unknown" in b.status_string(99)
 
 

@@ -43,6 +43,24 @@ def test_fit_residual_is_orthogonal_to_the_regressors():
         assert abs(np.dot(r, reg)) <= 1e-7 * np.linalg.norm(reg) * np.linalg.norm(t)
 
 
+def test_weighted_fit_properties():
+    rng = np.random.default_rng(5)
+    l = rng.uniform(100, 5000, size=30)
+    t = 1e-6 * l * l + 1e-3 * l + 0.5 + rng.normal(0, 0.05, size=30)
+    w = rng.uniform(0.1, 3.0, size=30)
+    m = po.fit_latency(l, t, w)
+    r = t - np.array([po.latency(m, x) for x in l])
+    for reg in (l * l, l, np.ones_like(l)):              # weighted normal equations
+        assert abs(np.dot(w * r, reg)) <= 1e-7 * np.linalg.norm(reg) * np.linalg.norm(t) * w.max()
+    # integer weights are repetition counts
+    k = np.array([1, 2, 3, 1, 2, 1])
+    l6, t6 = l[:6], t[:6]
+    rep = po.fit_latency(np.repeat(l6, k), np.repeat(t6, k))
+    assert np.allclose(po.fit_latency(l6, t6, k.astype(float)), rep, rtol=1e-8)
+    # equal weights change nothing
+    assert np.allclose(po.fit_latency(l, t, np.full(30, 7.0)), po.fit_latency(l, t), rtol=1e-8)
+
+
 def test_fit_needs_three_distinct_lengths():
     with pytest.raises(ValueError):
         po.fit_latency([1, 1, 2], [1, 1, 2])
