@@ -4,9 +4,11 @@ Sec. 6.1 and App. C.2, D): fit T(l) = a l^2 + b l + c to the measured forward+ba
 sequences inside packed buffers, pack a length draw into micro-batches once the way the paper argues against
 (fill to the maximum length, first fit decreasing) and once by Eq. 1 (minimise the longest
 micro-batch times (PP - 1 + V), V enumerated), then run every micro-batch of both packings on the
-GPU and compare predicted with measured times.  Prints one JSON object.
+GPU and compare predicted with measured times.  With --dispatch the draw is first dispatched over
+four simulated pipelines (Sec. 6.2, Alg. 1 against length buckets).  Prints one JSON object.
 
     python -m paper_2412_07894_amd.packing_study --config 5 --pp 4
+    python -m paper_2412_07894_amd.packing_study --config 3 --pp 4 --dispatch
 """
 import argparse
 import json
@@ -103,17 +105,66 @@ def study(lengths, hq, hkv, d, max_len, pp, probe_lengths, reps=5, warmup=2, nod
     return out
 
 
+def dispatch_study(lengths, hq, hkv, d, max_lens, pps, trials, probe_lengths, reps=5, warmup=2, seed=0,
+                   node_limit=500_000):
+    """Sec. 6.2 on one GPU: the D pipelines are simulated one after the other with the same
+    kernels (one latency model), and differ in the longest sequence they admit and in depth.
+    Dispatches a mini-batch once by Alg. 1 and once by length buckets (every sequence to the
+    tightest pipeline that admits it: the naive approach of Sec. 6.2), packs each pipeline's share
+    by Eq. 1, runs every micro-batch and prices a pipeline at max micro-batch time x (PP-1+V)."""
+    import random
+    from . import planner
+    D = len(max_lens)
+    assert all(max_lens[j] >= max_lens[j + 1] for j in range(D - 1))
+    model, probe_ms = calibrate(hq, hkv, d, probe_lengths, max_lens[0], reps, warmup)
+    call_ms = time_lengths([64], hq, hkv, d, reps, warmup)
+    J = [sum(1 for m in max_lens if m >= l) for l in lengths]
+    rng = random.Random(seed)
+    perms = [rng.sample(range(len(lengths)), len(lengths)) for _ in range(trials)]
+    cost, greedy = planner.dispatch(lengths, J, [model] * D, pps, perms)
+    buckets = [j - 1 for j in J]
+    out = {"heads": [hq, hkv], "max_lens": list(max_lens), "pps": list(pps), "trials": trials,
+           "num_seqs": len(lengths), "tokens": int(sum(lengths)), "model_ms": dict(zip("abc", model.as_tuple())),
+           "call_overhead_ms": call_ms, "greedy_cost_bound_ms": cost}
+    for name, assign in (("length_buckets", buckets), ("greedy_alg1", greedy)):
+        pipes = []
+        for j in range(D):
+            mine = [int(l) for l, p in zip(lengths, assign) if p == j]
+            if not mine:
+                pipes.append({"seqs": 0, "tokens": 0, "V": 0, "bound_ms": 0.0, "measured_ms": 0.0})
+                continue
+            bound = sum(planner.latency(model, l) for l in mine) + planner.latency(model, max(mine)) * (pps[j] - 1)
+            _, V, a, _ = planner.pack(mine, model, max_lens[j], util_len(model, max_lens[j]), pps[j], node_limit)
+            batches = [[l for l, b in zip(mine, a) if b == k] for k in range(V)]
+            meas = [time_lengths(mb, hq, hkv, d, reps, warmup, seed=31 * j + k) for k, mb in enumerate(batches)]
+            pipes.append({"seqs": len(mine), "tokens": sum(mine), "V": V, "bound_ms": bound,
+                          "measured_ms": max(meas) * (pps[j] - 1 + V), "micro_batch_ms": meas})
+        out[name] = {"pipelines": pipes, "max_bound_ms": max(p["bound_ms"] for p in pipes),
+                     "max_measured_ms": max(p["measured_ms"] for p in pipes)}
+    out["measured_ratio_buckets_over_greedy"] = out["length_buckets"]["max_measured_ms"] / out["greedy_alg1"]["max_measured_ms"]
+    return out
+
+
 def main():
     from . import workloads as wl
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--pp", type=int, default=4)
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--dispatch", action="store_true",
+                    help="dispatch the draw over 4 simulated pipelines (Sec. 6.2) instead of packing one")
     args = ap.parse_args()
     cfg = wl.CONFIGS[args.config]
     lengths = [int(l) for l in wl.seqlens(args.config)]
     probes = [l for l in (256, 512, 1024, 2048, 4096, 8192, 12288, 16384, 24576, 32768, 49152, 65536)
               if l <= cfg.buffer_tokens]
+    if args.dispatch:
+        cap = cfg.buffer_tokens
+        res = dispatch_study(lengths, cfg.hq, cfg.hkv, cfg.d, [cap, cap // 2, cap // 4, cap // 4],
+                             [args.pp, args.pp, 2, 2], 100, probes, reps=args.reps)
+        res["workload"] = f"config {cfg.cid}: {cfg.name}"
+        print(json.dumps(res))
+        return 0
     res = study(lengths, cfg.hq, cfg.hkv, cfg.d, cfg.buffer_tokens, args.pp, probes, reps=args.reps)
     res["workload"] = f"config {cfg.cid}: {cfg.name}"
     print(json.dumps(res))

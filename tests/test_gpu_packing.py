@@ -29,3 +29,22 @@ def test_balanced_packing_against_max_length_packing():
         for pred, meas in zip(res[name]["predicted_ms"], res[name]["measured_ms"]):
             assert abs(pred - meas) <= 0.20 * meas, (name, pred, meas)
     assert res["balanced_eq1"]["measured_objective_ms"] <= 1.03 * res["max_length_ffd"]["measured_objective_ms"]
+
+
+def test_greedy_dispatch_against_length_buckets():
+    from paper_2412_07894_amd import packing_study as ps
+    rng = random.Random(8)
+    lengths = []
+    # an iteration without very long sequences: the case in which length buckets leave the
+    # pipelines built for long sequences idle (Sec. 6.2)
+    while sum(lengths) < 4 * 32768:
+        lengths.append(min(12000, max(64, int(512 * rng.random() ** (-1 / 1.1)))))
+    res = ps.dispatch_study(lengths, 32, 32, 128, [32768, 16384, 8192, 8192], [4, 4, 2, 2], 50,
+                            [512, 1024, 2048, 4096, 8192, 16384, 24576, 32768], reps=5, warmup=2, seed=1)
+    print(res)
+    for name in ("length_buckets", "greedy_alg1"):
+        for p in res[name]["pipelines"]:
+            # Eq. 2 is a lower bound of the pipeline's time (up to the model's error)
+            assert p["bound_ms"] <= 1.10 * p["measured_ms"] + 0.2, (name, p)
+    assert res["greedy_alg1"]["max_measured_ms"] <= 1.03 * res["length_buckets"]["max_measured_ms"]
+    assert res["greedy_alg1"]["max_bound_ms"] <= res["length_buckets"]["max_bound_ms"] * (1 + 1e-9)
