@@ -115,9 +115,10 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
         }
     }
     constexpr int kCAhead = 4;
-    bf16x8 cf[kCAhead];                       // K^T fragments for the dQ product, requested early
+    LdsQueue lq{0};
+    ColFrag cf[kCAhead];                      // K^T fragments for the dQ product, requested early
 #pragma unroll
-    for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(Kt, fa, 2 * kb + (i >> 2), i & 3);
+    for (int i = 0; i < kCAhead; ++i) issue_col(lq, cf[i], Kt, fa, 2 * kb + (i >> 2), i & 3);
     __builtin_amdgcn_sched_barrier(0);
     if (mask) {                               // hidden keys: P = exp2(-inf) = 0
 #pragma unroll
@@ -137,8 +138,8 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
 #pragma unroll
     for (int i = 0; i < 8; ++i) {             // i = 4*b2 + db
         const int b2 = i >> 2, db = i & 3;
-        acc[db] = mfma32(cf[i % kCAhead], as_bf16x8(dcur), acc[db]);
-        if (i + kCAhead < 8) cf[i % kCAhead] = frag_col(Kt, fa, 2 * kb + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
+        acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(dcur), acc[db]);
+        if (i + kCAhead < 8) issue_col(lq, cf[i % kCAhead], Kt, fa, 2 * kb + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
         if (b2 == 0) dnxt[db] = ds_pair(4 + db);
         __builtin_amdgcn_sched_barrier(0);
         if (i == 3) dcur = dnxt;
@@ -400,6 +401,9 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             const bool work = active && ifirst + 31 >= wkey0; // some row sees some key of the pair
             f32x16 x;
             uint32_t pk[8];
+            constexpr int kCAhead = 4;
+            LdsQueue lq{0};
+            ColFrag cf[kCAhead];
             if (work) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) x[r] = 0.f;
@@ -433,8 +437,18 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                         pk[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
                     }
                 }
+                // the first fragments of the second product are requested BEFORE the barrier (their
+                // tile has been resident since the step began), so that their latency runs under
+                // the barrier instead of after it.  LDS operations complete in order: once at most
+                // these 2 * kCAhead reads are outstanding, the P stores issued before them are done.
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < kCAhead; ++i) issue_col(lq, cf[i], T2, fa, 2 * ib + (i >> 2), i & 3);
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(0xc07f | ((2 * kCAhead) << 8));
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xc07f);
             }
-            __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): P is in LDS
             __builtin_amdgcn_s_barrier();
             if (work) {
                 if (role_b) {
@@ -446,17 +460,17 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                         pk[2 * rq + 1] = pack_bf16(pv[2] * (x[4 * rq + 2] - d4[2]), pv[3] * (x[4 * rq + 3] - d4[3]));
                     }
                 }
-                constexpr int kCAhead = 4;
-                bf16x8 cf[kCAhead];
+                // the bookkeeping of the reads issued before the barrier, restated as constants
+                lq.issued = 2 * kCAhead;
 #pragma unroll
-                for (int i = 0; i < kCAhead; ++i) cf[i] = frag_col(T2, fa, 2 * ib + (i >> 2), i & 3);
+                for (int i = 0; i < kCAhead; ++i) cf[i].seq = 2 * (i + 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {                 // i = 4*b2 + db
                     const int b2 = i >> 2, db = i & 3;
                     u32x4 bv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
-                    acc[db] = mfma32(cf[i % kCAhead], as_bf16x8(bv), acc[db]);
-                    if (i + kCAhead < 8) cf[i % kCAhead] = frag_col(T2, fa, 2 * ib + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
+                    acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(bv), acc[db]);
+                    if (i + kCAhead < 8) issue_col(lq, cf[i % kCAhead], T2, fa, 2 * ib + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }

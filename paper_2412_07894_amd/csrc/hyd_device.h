@@ -116,6 +116,58 @@ __device__ __forceinline__ bf16x8 frag_col(int tile, const FragAddr& fa, int b, 
     return as_bf16x8(v);
 }
 
+// ---- LDS fragment reads with explicit completion tracking
+//
+// The compiler cannot tell a direct-to-LDS load (global -> LDS without registers) apart from the
+// tiles the kernel is reading, so before an LDS read it knows to be one it drains the whole load
+// queue, the tiles requested for LATER steps included; that turns a ring of stages into a ring
+// of one.  The fragment reads of the hot loops are therefore issued as volatile assembly, which
+// keeps them in source order, and completion is tracked by hand: LDS reads return in order, so a
+// fragment has arrived once at most (reads issued after it) remain outstanding.  LdsQueue counts
+// issued read instructions; after full unrolling every count is a compile-time constant and goes
+// into the immediate of s_waitcnt.  The wait statement takes the fragment as an in/out operand, so
+// the consumer depends on the wait and the wait on the read, wherever the scheduler puts them.
+// Reads the compiler issues by itself in between only make these waits stricter than necessary.
+// Instruction offsets are 16-bit immediates; issue_row / issue_col move what exceeds them into the
+// address register (a compile-time constant per call site, so at most one add per address).
+struct LdsQueue { int issued; };
+struct RowFrag { u32x4 v; int seq; };
+struct ColFrag { u32x2 lo, hi; int seq; };
+
+__device__ __forceinline__ void lds_issue_row(LdsQueue& q, RowFrag& f, uint32_t addr, int off) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(addr), "i"(off));
+    f.seq = ++q.issued;
+}
+__device__ __forceinline__ void lds_issue_col(LdsQueue& q, ColFrag& f, uint32_t addr_lo, uint32_t addr_hi, int off) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(addr_lo), "i"(off));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr_hi), "i"(off));
+    q.issued += 2;
+    f.seq = q.issued;
+}
+__device__ __forceinline__ bf16x8 lds_wait(const LdsQueue& q, RowFrag& f) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f.v) : "i"(q.issued - f.seq < 15 ? q.issued - f.seq : 15));
+    return as_bf16x8(f.v);
+}
+__device__ __forceinline__ bf16x8 lds_wait(const LdsQueue& q, ColFrag& f) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(f.lo), "+v"(f.hi) : "i"(q.issued - f.seq < 15 ? q.issued - f.seq : 15));
+    u32x4 v = {f.lo[0], f.lo[1], f.hi[0], f.hi[1]};
+    return as_bf16x8(v);
+}
+// Row fragment (blk, ks) / column fragment (b, cb) of the tile at byte offset `tile` (see frag_row
+// and frag_col for the meaning of the indices).
+__device__ __forceinline__ void issue_row(LdsQueue& q, RowFrag& f, int tile, const FragAddr& fa, int blk, int ks) {
+    const int off = tile + blk * 32 * kRowBytes, hi = off & ~0xffff;
+    lds_issue_row(q, f, fa.row[ks] + (uint32_t)hi, off - hi);
+}
+__device__ __forceinline__ void issue_col(LdsQueue& q, ColFrag& f, int tile, const FragAddr& fa, int b, int cb) {
+    const int off = tile + b * 16 * kRowBytes, hi = off & ~0xffff;
+    lds_issue_col(q, f, fa.col[2 * cb] + (uint32_t)hi, fa.col[2 * cb + 1] + (uint32_t)hi, off - hi);
+}
+// Keeps a value's computation where the source puts it (the optimiser otherwise sinks work into
+// the block of its first use).
+__device__ __forceinline__ void pin(uint32_t& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
+
 // Buffer resource over `bytes` bytes starting at `base`: loads beyond the range return zero, which
 // is how the tails of a sequence are zero-filled without branches.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
