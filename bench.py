@@ -109,6 +109,26 @@ def run_gpu(cid, steps, warmup, inputs="randn"):
     return cfg, lengths, pairs, ms_per_step, kernels
 
 
+def per_buffer(cid, reps=5, warmup=2):
+    """The paper's micro-batch view (Sec. 2.1, Fig. 2): one forward+backward call per packed buffer
+    of the configuration, one after the other; equal token counts, very different times."""
+    from paper_2412_07894_amd import packing_study, workloads as wl
+    cfg = wl.CONFIGS[cid]
+    lengths = [int(l) for l in wl.seqlens(cid)]
+    buffers, cur = [], []
+    for l in lengths:                       # buffers are exactly full and listed one after the other
+        cur.append(l)
+        if sum(cur) == cfg.buffer_tokens:
+            buffers.append(cur)
+            cur = []
+    if cur or len(buffers) != cfg.n_buffers:
+        return None
+    ms = [packing_study.time_lengths(b, cfg.hq, cfg.hkv, cfg.d, reps, warmup, seed=i) for i, b in enumerate(buffers)]
+    tf = [14.0 * cfg.d * cfg.hq * wl.causal_pairs(b) / 1e12 for b in buffers]
+    return {"tokens_per_buffer": cfg.buffer_tokens, "seqs": [len(b) for b in buffers], "longest": [max(b) for b in buffers],
+            "ms": ms, "useful_tflop": tf, "max_over_min_ms": max(ms) / min(ms), "sum_ms": sum(ms)}
+
+
 def cpu_baseline(cid):
     """The fp64 oracle, as it stands, on a bounded sample of the workload (about 2-3e12 flop,
     10-30 s on 16 cores): as many KV groups as the oracle has threads (its OpenMP loop runs over
@@ -166,6 +186,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--inputs", default="randn", choices=["randn", "zeros"])
+    ap.add_argument("--per-buffer", action="store_true", help="also time one call per packed buffer")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU hot path (no collectives, no sharding); run with --gpus 1")
@@ -196,6 +217,8 @@ def main():
                            "avg_ms": kernels[dom]}
     if not args.no_mfma_probe and cfg.dtype == "bf16":
         out["mfma_probe"] = mfma_probe()
+    if args.per_buffer and cfg.dtype == "bf16":
+        out["per_buffer"] = per_buffer(args.config)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))
