@@ -82,9 +82,10 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     }
     // the first V fragments are requested now, so that their latency hides behind the softmax
     constexpr int kVAhead = 4;
-    bf16x8 vf[kVAhead];
+    LdsQueue lq{0};
+    ColFrag vf[kVAhead];
 #pragma unroll
-    for (int i = 0; i < kVAhead; ++i) vf[i] = frag_col(Vt, fa, i >> 2, i & 3);
+    for (int i = 0; i < kVAhead; ++i) issue_col(lq, vf[i], Vt, fa, i >> 2, i & 3);
     __builtin_amdgcn_sched_barrier(0);
     if (diag) {         // hidden keys score -inf (scale_log2 > 0 always, so exp2 turns them into 0)
         const int k0 = diag_first ? krel : krel - 32;     // key-minus-row offset of block 0
@@ -135,8 +136,8 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
 #pragma unroll
     for (int i = 0; i < 16; ++i) {                      // i = 4*b + db
         const int b = i >> 2, db = i & 3;
-        acc_o[db] = mfma32(vf[i % kVAhead], as_bf16x8(pcur), acc_o[db]);
-        if (i + kVAhead < 16) vf[i % kVAhead] = frag_col(Vt, fa, (i + kVAhead) >> 2, (i + kVAhead) & 3);
+        acc_o[db] = mfma32(lds_wait(lq, vf[i % kVAhead]), as_bf16x8(pcur), acc_o[db]);
+        if (i + kVAhead < 16) issue_col(lq, vf[i % kVAhead], Vt, fa, (i + kVAhead) >> 2, (i + kVAhead) & 3);
         if (b < 3) pnxt[db] = exp_pair(4 * (b + 1) + db);
         __builtin_amdgcn_sched_barrier(0);
         if (db == 3) pcur = pnxt;
