@@ -36,7 +36,7 @@ WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
     w.cnt_ge = at; at += lev_bytes;
     w.offs = at;   at += lev_bytes;
     w.fill = at;   at += lev_bytes;
-    w.items = at;  at += align_up(sizeof(int) * 2 * (size_t)w.max_items);
+    w.items = at;  at += align_up(sizeof(int) * 4 * (size_t)w.max_items);
     w.dvec = at;
     if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
     w.lse2vec = at;

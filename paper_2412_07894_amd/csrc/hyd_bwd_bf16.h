@@ -167,13 +167,11 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
     // only the score product reads; a zero scale becomes an epsilon so that -inf * scale = -inf
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
-    const int krel = 4 * half - l32;
 
     WorkFetcher wf;
     WorkItem wi;
-    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi);
     while (have) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kDqBM;
@@ -241,6 +239,9 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             else if (t + 1 < n_kt) dma_tile(t + 1, STN);
             if (active && t <= td) {
                 const bool diag = t == td;
+                // key-minus-row offset of the masked block, formed from the tile index so that the
+                // mask comparisons are not hoisted out of the tile loop into scalar registers
+                const int krel = t * kDqBN + 32 * diag_kb + 4 * half - qrow;
                 dq_block(Kt, Vt, fa, 0, qf, dof, acc, scale_log2, lse2, Dq, diag && diag_kb == 0, krel);
                 if (!(diag && diag_kb == 0))
                     dq_block(Kt, Vt, fa, 1, qf, dof, acc, scale_log2, lse2, Dq, diag, krel);
@@ -263,7 +264,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
         }
         if (qvalid)
             store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
-        have = wf.next(slot, wi);
+        have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 2, t_start, n_done);
 }
@@ -325,9 +326,8 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 
     WorkFetcher wf;
     WorkItem wi;
-    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi);
     while (have) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
         const int lev = wi.lev, g = wi.head, row0 = wi.row0, L = wi.len;
         const int n_tiles = (L + kKvBN - 1) / kKvBN;
@@ -501,7 +501,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             if (role_b) store_rows_bf16(p.dk + off, acc, p.scale, half);
             else store_rows_bf16(p.dv + off, acc, 1.f, half);
         }
-        have = wf.next(slot, wi);
+        have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 1, t_start, n_done);
 }

@@ -38,8 +38,7 @@ __global__ void __launch_bounds__(kF32Tile) hyd_fwd_fp32_kernel(F32Params p) {
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
     WorkItem wi;
-    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi); have; have = wf.next(p.hm, p.cursors, p.items, slot, wi)) {
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kF32Tile;
         const int i = q0 + tid;
@@ -97,8 +96,7 @@ __global__ void __launch_bounds__(kF32Tile) hyd_bwd_dq_fp32_kernel(F32Params p) 
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
     WorkItem wi;
-    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi); have; have = wf.next(p.hm, p.cursors, p.items, slot, wi)) {
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kF32Tile;
         const int i = q0 + tid;
@@ -138,8 +136,7 @@ __global__ void __launch_bounds__(kF32Tile) hyd_bwd_dkdv_fp32_kernel(F32Params p
     const int G = p.hq / p.hkv;
     WorkFetcher wf;
     WorkItem wi;
-    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi); have; have = wf.next(slot, wi)) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
+    for (bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi); have; have = wf.next(p.hm, p.cursors, p.items, slot, wi)) {
         const int lev = wi.lev, g = wi.head, row0 = wi.row0, L = wi.len;
         const int n_tiles = (L + kF32Tile - 1) / kF32Tile;
         const int j0 = (n_tiles - lev) * kF32Tile;

@@ -55,10 +55,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 // One 64-key tile for the 32 rows of a wave.  There is ONE body for all tiles (separate bodies for
 // masked and unmasked tiles make the compiler keep the accumulators twice and copy them at every
 // join); only the masking itself sits in a wave-uniform branch.  `diag`: this is the wave's
-// diagonal tile; `diag_first`: its diagonal block is the tile's first block, the second is hidden.
+// diagonal tile (its second 32-key block may be hidden altogether).
 __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, const bf16x8 (&qf)[8],
                                          f32x16 (&acc_o)[4], float& m_ref, float& l_run, float scale_log2,
-                                         int krel, bool diag, bool diag_first) {
+                                         int koff, bool diag) {
     // The instruction order below is pinned with scheduling fences: left alone, the compiler sinks
     // every LDS read next to its use and serialises read -> wait -> MFMA.
     f32x16 s[2];
@@ -88,7 +88,11 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     for (int i = 0; i < kVAhead; ++i) issue_col(lq, vf[i], Vt, fa, i >> 2, i & 3);
     __builtin_amdgcn_sched_barrier(0);
     if (diag) {         // hidden keys score -inf (scale_log2 > 0 always, so exp2 turns them into 0)
-        const int k0 = diag_first ? krel : krel - 32;     // key-minus-row offset of block 0
+        // koff = position of the tile's first key slot of this lane minus the lane's query row.
+        // It is formed from the tile index, so that these 32 comparisons stay inside this rarely
+        // taken branch (as loop invariants they would be hoisted into 64 scalar registers and
+        // spilled at every item).
+        const int k0 = koff;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -168,13 +172,11 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
     // (and a zero scale becomes a denormal-free epsilon, so that -inf * scale stays -inf)
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
-    const int krel = 4 * half - l32;
 
     WorkFetcher wf;
     WorkItem wi;
-    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, p.cu, slot, wi);
+    bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi);
     while (have) {
-        wf.prefetch(p.hm, p.hdr, p.cursors, p.items, p.cu, slot);
         ++n_done;
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kFwdBM;
@@ -186,7 +188,7 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         const bool qvalid = qrow < L;
         const bool active = wrow0 < L;                    // else the wave only helps with the loads
         const int td = wrow0 / kFwdBN;                    // this wave's diagonal (= last) tile
-        const bool diag_first = (wrow0 % kFwdBN) == 0;    // diagonal block is the tile's first block
+        const int koff0 = 4 * half - qrow;                // first key slot of the lane minus its query row, tile 0
         // K/V rows [0, kv_end) of this sequence and KV head; reads past them return zero
         const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowBytes;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
@@ -234,7 +236,8 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             const bool more2 = kFwdStages == 3 && t + 2 < n_kt;
             if (kFwdStages == 3) { if (more2) dma_tile(t + 2, ST2); }
             else if (t + 1 < n_kt) dma_tile(t + 1, STN);
-            if (active && t <= td) fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, krel, t == td, diag_first);
+            if (active && t <= td)
+                fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, t * kFwdBN + koff0, t == td);
             if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
             else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
@@ -269,7 +272,7 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
                 p.lse[(int64_t)head * p.T + row0 + qrow] =
                     (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
         }
-        have = wf.next(slot, wi);
+        have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 0, t_start, n_done);
 }

@@ -29,7 +29,7 @@ struct SchedView {            // device pointers into the workspace (all int32)
     int* cnt_ge;              // n_lev + 2 : number of sequences with >= c tiles
     int* offs;                // n_lev + 2 : first list position of level c
     int* fill;                // n_lev + 2 : scratch counters
-    int* items;               // 2 * max_items : (s, c) pairs, decreasing c
+    int* items;               // 4 * max_items : records (s, c, first packed row, length), decreasing c
     int n_lev;                // upper bound on tiles per sequence
     int max_items;
 };
@@ -100,7 +100,10 @@ __global__ void __launch_bounds__(1024) hyd_schedule_prelude(const int32_t* __re
         for (int c = 1; c <= n; ++c) {
             const int r = nl - c;
             const int pos = sv.offs[r] - sv.cnt_ge[r] + rank;
-            if (pos < sv.max_items) { sv.items[2 * pos] = s; sv.items[2 * pos + 1] = c; }
+            if (pos < sv.max_items) {
+                sv.items[4 * pos] = s; sv.items[4 * pos + 1] = c;
+                sv.items[4 * pos + 2] = cu[s]; sv.items[4 * pos + 3] = L;
+            }
         }
     }
 }
@@ -123,42 +126,64 @@ __device__ __forceinline__ void decode_work(const HeadMap& hm, int x, int w, int
     }
 }
 
-// Persistent-workgroup work fetch.  Thread 0 takes the next index of the current queue, moving on
-// to the next queue when one is exhausted, resolves it to (sequence, level, head) and to the
-// sequence's first packed row and length, and leaves the result in LDS.  The fetch of item k+1
-// is issued at the START of item k (prefetch), so its chain of dependent global accesses (cursor
-// atomic, item list, cu_seqlens) overlaps item k's tile loop; only wave 0, which owns the rows
-// with the shortest causal span, waits for it.  Every workgroup ends when all queues are empty
+// Persistent-workgroup work fetch.  Thread 0 takes work indices from the queue of its XCD through
+// an atomic cursor, moving on to the next queue when one is exhausted, resolves an index to
+// (item, head), fetches the item's 16-byte record and leaves the result in LDS for the workgroup.
+//
+// The chain "cursor atomic -> item record" is two dependent trips to memory, as long as a whole
+// short item, so the atomic is taken off the critical path: the one for item k+1 is issued when
+// item k begins (in next(), right after the barrier that ends item k-1) and its result is only
+// looked at when item k ends, an item's duration later.  What remains at the end of an item is
+// one trip for the record.  A workgroup thus holds one claimed item ahead of the one it works on
+// (holding two, with the record fetched early as well, costs more balance at the end of a launch
+// than it saves).  Only when a queue runs dry (eight times in a workgroup's life) is a claim
+// repeated on the next queue synchronously.  Every workgroup ends when all queues are empty
 // (the cursors only grow).
 struct WorkItem { int seq, lev, head, row0, len; };
 constexpr int kSlotInts = 16;          // two buffers of 8 ints
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 struct WorkFetcher {
-    int queue;      // current queue
-    int tried;      // queues found empty so far
-    int cur;        // slot buffer holding the current item
-    __device__ __forceinline__ void fetch_into(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
-                                               const int* __restrict__ items, const int32_t* __restrict__ cu,
-                                               int* buf) {
-        const int n_items = hdr[0];
-        int item = -1, hd = 0;
+    int cur;          // slot buffer holding the current item (all threads)
+    // the rest is thread 0's
+    int queue;        // queue the next claim goes to
+    int tried;        // queues found empty so far
+    int n_items;
+    int claim_q;      // queue of the claim in flight
+    int claim_w;      // its result (the atomic's return value; no use of it until one item later)
+    int nxt_item;     // next item: index (-1: none), head, and its record in flight
+    int nxt_head;
+    i32x4 nxt_rec;
+
+    __device__ __forceinline__ void issue_claim(const HeadMap& hm, int* cursors) {
+        claim_q = queue;
+        const bool open = tried < kQueues && queue_size(hm, n_items, queue) > 0;
+        claim_w = open ? atomicAdd(&cursors[queue], 1) : 0x7fffffff;
+    }
+    // Turns the claim in flight into (item, head) of the next item and requests its record.
+    __device__ __forceinline__ void resolve(const HeadMap& hm, int* cursors, const int* __restrict__ items) {
+        int q = claim_q, w = claim_w;
+        nxt_item = -1;
+        nxt_head = 0;
         while (tried < kQueues) {
-            const int size = queue_size(hm, n_items, queue);
-            int w = size > 0 ? atomicAdd(&cursors[queue], 1) : size;
-            if (w < size) { decode_work(hm, queue, w, item, hd); break; }
-            queue = (queue + 1) & (kQueues - 1);
-            ++tried;
+            if (w < queue_size(hm, n_items, q)) {
+                decode_work(hm, q, w, nxt_item, nxt_head);
+                break;
+            }
+            if (q == queue) {                       // that queue is exhausted: on to the next one
+                queue = (queue + 1) & (kQueues - 1);
+                ++tried;
+                if (tried >= kQueues) break;
+            }
+            q = queue;
+            w = queue_size(hm, n_items, q) > 0 ? atomicAdd(&cursors[q], 1) : 0x7fffffff;
         }
-        buf[0] = item;
-        buf[1] = hd;
-        if (item >= 0) {
-            const int sq = items[2 * item];
-            buf[2] = sq;
-            buf[3] = items[2 * item + 1];
-            const int r0 = cu[sq];
-            buf[4] = r0;
-            buf[5] = cu[sq + 1] - r0;
-        }
+        if (nxt_item >= 0) nxt_rec = *reinterpret_cast<const i32x4*>(items + 4 * nxt_item);
+    }
+    __device__ __forceinline__ void publish(int* buf) const {
+        buf[0] = nxt_item;
+        buf[1] = nxt_head;
+        if (nxt_item >= 0) { buf[2] = nxt_rec[0]; buf[3] = nxt_rec[1]; buf[4] = nxt_rec[2]; buf[5] = nxt_rec[3]; }
     }
     __device__ __forceinline__ bool read(const int* buf, WorkItem& w) const {
         if (buf[0] < 0) return false;
@@ -167,23 +192,28 @@ struct WorkFetcher {
     }
     // `slot`: kSlotInts ints of LDS.  All threads must call first/next (each contains a barrier).
     __device__ __forceinline__ bool first(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
-                                          const int* __restrict__ items, const int32_t* __restrict__ cu,
-                                          int* slot, WorkItem& w) {
-        queue = (__smid() >> 6) & (kQueues - 1);     // XCC id of this workgroup
-        tried = 0;
+                                          const int* __restrict__ items, int* slot, WorkItem& w) {
         cur = 0;
-        if (threadIdx.x == 0) fetch_into(hm, hdr, cursors, items, cu, slot);
+        if (threadIdx.x == 0) {
+            queue = (__smid() >> 6) & (kQueues - 1);     // XCC id of this workgroup
+            tried = 0;
+            n_items = hdr[0];
+            issue_claim(hm, cursors);
+            resolve(hm, cursors, items);
+            publish(slot);
+        }
         __syncthreads();
+        if (threadIdx.x == 0) issue_claim(hm, cursors);  // for the item after the first
         return read(slot, w);
     }
-    // call right after first()/next() returned true
-    __device__ __forceinline__ void prefetch(const HeadMap& hm, const int* __restrict__ hdr, int* cursors,
-                                             const int* __restrict__ items, const int32_t* __restrict__ cu,
-                                             int* slot) {
-        if (threadIdx.x == 0) fetch_into(hm, hdr, cursors, items, cu, slot + 8 * (cur ^ 1));
-    }
-    __device__ __forceinline__ bool next(int* slot, WorkItem& w) {
-        __syncthreads();        // the prefetched item is visible; everybody is done with the LDS tiles
+    __device__ __forceinline__ bool next(const HeadMap& hm, int* cursors, const int* __restrict__ items,
+                                         int* slot, WorkItem& w) {
+        if (threadIdx.x == 0) {
+            resolve(hm, cursors, items);                 // the claim issued when this item began
+            publish(slot + 8 * (cur ^ 1));
+        }
+        __syncthreads();        // the next item is visible; everybody is done with the LDS tiles
+        if (threadIdx.x == 0) issue_claim(hm, cursors);  // for the item after the next
         cur ^= 1;
         return read(slot + 8 * cur, w);
     }
