@@ -248,7 +248,7 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
         FwdParams p;
         p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
         p.v = static_cast<const uint16_t*>(v); p.o = static_cast<uint16_t*>(o); p.lse = lse;
-        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv;
+        p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale_log2 = softmax_scale * kLog2e;
         p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
         KernelTimer kt("fwd_bf16", st);
@@ -259,7 +259,7 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
         memset(&p, 0, sizeof(p));
         p.q = static_cast<const float*>(q); p.k = static_cast<const float*>(k);
         p.v = static_cast<const float*>(v); p.o_out = static_cast<float*>(o); p.lse_out = lse;
-        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
+        p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
         p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
         const int grid = persistent_grid(*dev, 8, work);
         KernelTimer kt("fwd_fp32", st);
@@ -311,7 +311,7 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
         p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
         p.lse2 = Lse2; p.D = Dvec;
         p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
-        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv;
+        p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
         p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
         {
@@ -337,7 +337,7 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
         p.v = static_cast<const float*>(v); p.o = static_cast<const float*>(o);
         p.d_o = static_cast<const float*>(d_o); p.lse_in = lse; p.D = Dvec;
         p.dq = static_cast<float*>(dq); p.dk = static_cast<float*>(dk); p.dv = static_cast<float*>(dv);
-        p.cu = cu_seqlens; p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
+        p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
         p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
         const unsigned rd_grid = (unsigned)((n_rows + 255) / 256);
         const int grid_q = persistent_grid(*dev, 8, work_q), grid_kv = persistent_grid(*dev, 2, work_kv);

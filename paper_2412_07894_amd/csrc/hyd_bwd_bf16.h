@@ -48,7 +48,6 @@ struct BwdParams {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
     const float* lse2; const float* D;      // LSE * log2(e) and rowsum(dO * O), both [Hq][T]
     uint16_t* dq; uint16_t* dk; uint16_t* dv;
-    const int32_t* cu;
     int T, hq, hkv;
     float scale, scale_log2;
     const int* hdr; int* cursors; const int* items;

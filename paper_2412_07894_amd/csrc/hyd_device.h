@@ -1,5 +1,5 @@
 // Device-side building blocks shared by the gfx950 attention kernels: vector types, the MFMA
-// wrapper with its operand/accumulator lane maps, the LDS tile layout, and global<->LDS movers.
+// wrapper with its operand/accumulator lane maps, the LDS tile layout and the fragment reads.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,7 +14,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kWave = 64;
 constexpr int kHeadDim = 128;                 // bf16 path
@@ -56,7 +55,6 @@ __device__ __forceinline__ int tile_off(int row, int chunk) {     // byte offset
     return row * kRowBytes + ((chunk ^ swz(row)) << 4);
 }
 
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // Transposing read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane i supplies the
 // address of a 4-element row fragment; lane L then receives element L % 4 of the fragments
@@ -104,18 +102,6 @@ __device__ __forceinline__ bf16x8 frag_row(int tile, const FragAddr& fa, int blk
     return as_bf16x8(*(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(tile + blk * 32 * kRowBytes)));
 }
 
-// Column fragment (contraction index = tile row): step b (16 rows), column
-// block cb (32 columns).
-__device__ __forceinline__ bf16x8 frag_col(int tile, const FragAddr& fa, int b, int cb) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(fa.col[2 * cb] + (uint32_t)(tile + b * 16 * kRowBytes)));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(fa.col[2 * cb + 1] + (uint32_t)(tile + b * 16 * kRowBytes)));
-    u32x2 l2, h2;
-    __builtin_memcpy(&l2, &lo, 8);
-    __builtin_memcpy(&h2, &hi, 8);
-    u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
-    return as_bf16x8(v);
-}
-
 // ---- LDS fragment reads with explicit completion tracking
 //
 // The compiler cannot tell a direct-to-LDS load (global -> LDS without registers) apart from the
@@ -153,8 +139,9 @@ __device__ __forceinline__ bf16x8 lds_wait(const LdsQueue& q, ColFrag& f) {
     u32x4 v = {f.lo[0], f.lo[1], f.hi[0], f.hi[1]};
     return as_bf16x8(v);
 }
-// Row fragment (blk, ks) / column fragment (b, cb) of the tile at byte offset `tile` (see frag_row
-// and frag_col for the meaning of the indices).
+// Row fragment (blk, ks) of the tile at byte offset `tile` (indices as in frag_row); column
+// fragment (contraction index = tile row): contraction step b (16 rows), column block cb (32
+// columns), two transposing reads matched to the accumulator lane map as described above.
 __device__ __forceinline__ void issue_row(LdsQueue& q, RowFrag& f, int tile, const FragAddr& fa, int blk, int ks) {
     const int off = tile + blk * 32 * kRowBytes, hi = off & ~0xffff;
     lds_issue_row(q, f, fa.row[ks] + (uint32_t)hi, off - hi);
@@ -173,40 +160,6 @@ __device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
-
-// Global -> registers -> LDS copy of a [ROWS][128] bf16 tile by NT threads.  Thread t moves the
-// 16-byte chunks (row t/16 + 16*p, chunk t%16), p = 0..ROWS/16*... ; rows beyond the buffer
-// resource's range arrive as zeros.
-template <int ROWS, int NT>
-struct TileMover {
-    static constexpr int kChunks = ROWS * kChunksPerRow;
-    static constexpr int kPerThread = kChunks / NT;
-    static constexpr int kRowStep = NT / kChunksPerRow;          // rows between a thread's chunks
-    static_assert(kChunks % NT == 0, "tile must divide over the threads");
-    static_assert(kRowStep % 16 == 0, "swz() must not change between a thread's chunks");
-    u32x4 reg[kPerThread];
-    uint32_t voff;        // byte offset of (row t/16, chunk t%16) from the resource base
-    uint32_t lds_off;     // LDS byte offset of the same chunk within a tile
-    uint32_t step_bytes;  // kRowStep rows in bytes
-
-    __device__ __forceinline__ void init(int tid, uint32_t row_stride_bytes) {
-        const int r = tid / kChunksPerRow, c = tid % kChunksPerRow;
-        voff = r * row_stride_bytes + c * 16;
-        lds_off = tile_off(r, c);
-        step_bytes = kRowStep * row_stride_bytes;
-    }
-    // tile_byte_off: byte offset of the tile's first row from the resource base (wave-uniform)
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, uint32_t tile_byte_off) {
-#pragma unroll
-        for (int p = 0; p < kPerThread; ++p)
-            reg[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, tile_byte_off + p * step_bytes, 0);
-    }
-    __device__ __forceinline__ void store(char* tile) const {
-#pragma unroll
-        for (int p = 0; p < kPerThread; ++p)
-            *reinterpret_cast<u32x4*>(tile + lds_off + p * kRowStep * kRowBytes) = reg[p];
-    }
-};
 
 __device__ __forceinline__ float shfl_xor32(float v) {
     // exchange with the lane 32 away (the other half of the wave)

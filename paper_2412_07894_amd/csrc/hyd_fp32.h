@@ -15,7 +15,6 @@ struct F32Params {
     const float* lse_in; const float* D;
     float* o_out; float* lse_out; float* D_out;
     float* dq; float* dk; float* dv;
-    const int32_t* cu;
     int T, hq, hkv;
     float scale;
     const int* hdr; int* cursors; const int* items;

@@ -42,7 +42,6 @@ constexpr float kRefSlack = 8.f;                                  // log2 units,
 struct FwdParams {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;
     uint16_t* o; float* lse;
-    const int32_t* cu;
     int T, hq, hkv;
     float scale_log2;                 // softmax_scale * log2(e)
     const int* hdr; int* cursors; const int* items;
