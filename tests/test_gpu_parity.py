@@ -11,8 +11,9 @@ import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-def full_parity(lengths, hq, hkv, d, dtype, seed, scale=None, host_cu=True):
+def full_parity(lengths, hq, hkv, d, dtype, seed, scale=None, host_cu=True, grad_gain=1.0):
     cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, dtype, seed)
+    do = do * np.float32(grad_gain)          # a power of two: stays exactly representable
     scale = 1.0 / np.sqrt(d) if scale is None else scale
     print(f"\ncase lengths={list(lengths)[:12]}{'...' if len(lengths) > 12 else ''} hq={hq} hkv={hkv} d={d} {dtype} seed={seed} scale={scale}", flush=True)
     got = gu.run_gpu(cu, q, k, v, do, dtype, scale, host_cu=host_cu)
@@ -58,6 +59,24 @@ def test_fp32_small(lengths, hq, hkv, d):
 ])
 def test_bf16_small(lengths, hq, hkv):
     full_parity(lengths, hq, hkv, 128, "bf16", seed=31)
+
+
+def test_bf16_thousands_of_short_sequences():
+    # more sequences than the schedule prelude has threads, every item a single partial tile,
+    # empty sequences in between
+    rng = np.random.default_rng(5)
+    lengths = [int(x) for x in rng.integers(0, 41, size=3000)]
+    # 180 million output elements: with unit-variance dO a handful of gradient entries of size
+    # 3-10 would sit a few 1e-3 beyond the absolute bar through nothing but the bf16 rounding of
+    # P, dS and the output (this case is about the scheduler, so the upstream gradient is scaled)
+    full_parity(lengths, 8, 2, 128, "bf16", seed=41, grad_gain=0.25)
+
+
+def test_bf16_one_long_sequence_among_tiny_ones():
+    # levels 1..24 from one sequence only, next to many one-tile sequences: long ramp in the item
+    # list, queues that run dry at different times (work stealing)
+    lengths = [3, 6100, 1, 17, 64, 2, 255, 9]
+    full_parity(lengths, 6, 3, 128, "bf16", seed=43)
 
 
 def test_bf16_without_host_seqlens_and_other_scale():
