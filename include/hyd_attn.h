@@ -53,7 +53,8 @@ typedef enum {
     HYD_ERR_WORKSPACE = 7,  /* workspace NULL, misaligned (256 B) or smaller than required */
     HYD_ERR_ARCH = 8,       /* the current device is not gfx950 */
     HYD_ERR_LAUNCH = 9,     /* a HIP launch or query failed */
-    HYD_ERR_INFEASIBLE = 10 /* planning calls (hyd_plan.h): the constraints admit no solution */
+    HYD_ERR_INFEASIBLE = 10,/* planning calls (hyd_plan.h): the constraints admit no solution */
+    HYD_ERR_RANGE = 11      /* range variants: a range is misaligned or has end < begin */
 } hyd_status;
 
 typedef enum { HYD_BF16 = 0, HYD_FP32 = 1 } hyd_dtype;
@@ -118,6 +119,76 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
                                float softmax_scale, hyd_dtype dt,
                                void* dq, void* dk, void* dv,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Range variants: the building block of context parallelism (CP, one axis of the paper's
+ * <TP, PP, CP> schemes, Sec. 2.1 and App. C.1).  Under CP a device holds one chunk of every
+ * sequence's queries while the key/value chunks visit it one after the other; each visit
+ * computes the attention of a query range against a key range, and the partial results are
+ * merged by the log-sum-exp rule (hyd_attn_merge).  The calls below do one such visit for all
+ * sequences of a packed buffer; the buffers keep the layout of the plain calls (whole
+ * sequences, T rows), the ranges select what is computed.
+ *
+ *   ranges           device int32[4 * num_seqs]: per sequence (q_begin, q_end, kv_begin, kv_end)
+ *                    in LOCAL positions of the sequence.  Begins are multiples of
+ *                    HYD_RANGE_ALIGN; an end is a multiple of it too, or lies at or past the end
+ *                    of the sequence (it is then capped there).  end >= begin >= 0.  An empty
+ *                    range is allowed.
+ *   ranges_host      host copy or NULL; when given, the rules above are checked (HYD_ERR_RANGE;
+ *                    exactly if cu_seqlens_host is given too, else against max_seqlen).  Ranges
+ *                    that break the rules without a host copy give wrong values for the
+ *                    sequences concerned, never an access outside the buffers.
+ *   dt               HYD_BF16 only (HYD_ERR_DTYPE otherwise)
+ * Forward: for local row i of the query range, over the keys j of the key range with j <= i,
+ *     LSE_i = ln sum_j exp(s_ij),  O_i = sum_j exp(s_ij - LSE_i) V_j;
+ * a row that sees no such key gets O_i = 0 and LSE_i = -inf.  Rows outside the query range are
+ * NOT written.
+ */
+#define HYD_RANGE_ALIGN 256
+
+hyd_status hyd_varlen_attn_fwd_range(const void* q, const void* k, const void* v,
+                                     const int32_t* cu_seqlens, int num_seqs,
+                                     const int32_t* cu_seqlens_host,
+                                     const int32_t* ranges, const int32_t* ranges_host,
+                                     int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                                     float softmax_scale, hyd_dtype dt,
+                                     void* o, float* lse,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of one visit.  o and lse are the MERGED forward results of the rows (their full
+ * softmax over all visible keys), so that P_ij = exp(s_ij - LSE_i) and D_i = <dO_i, O_i> are the
+ * true ones; with them
+ *     dq rows of the query range = scale * sum_{j in key range, j <= i} dS_ij K_j
+ *     dk / dv rows of the key range = the sums of hyd_varlen_attn_bwd restricted to the rows i of
+ *                                  the query range.
+ * Summed over a partition of the keys (dq) or of the queries (dk, dv) they give the gradients
+ * of the plain call; the sum is the caller's (each call rounds its partial to the buffer's
+ * dtype).  Rows of dq outside the query range and rows of dk / dv outside the key range are NOT
+ * written.  Other arguments as hyd_varlen_attn_bwd / hyd_varlen_attn_fwd_range.
+ */
+hyd_status hyd_varlen_attn_bwd_range(const void* q, const void* k, const void* v, const void* o,
+                                     const float* lse, const void* d_o,
+                                     const int32_t* cu_seqlens, int num_seqs,
+                                     const int32_t* cu_seqlens_host,
+                                     const int32_t* ranges, const int32_t* ranges_host,
+                                     int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                                     float softmax_scale, hyd_dtype dt,
+                                     void* dq, void* dk, void* dv,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Log-sum-exp merge of two partial results over the same T rows (all device pointers;
+ * o_* [T][Hq][d] in dt, lse_* float [Hq][T], natural log):
+ *     LSE = ln(exp(LSE_a) + exp(LSE_b)),  O = exp(LSE_a - LSE) O_a + exp(LSE_b - LSE) O_b.
+ * A row whose LSE is -inf in one partial takes the other partial unchanged (whatever bits that
+ * row of the -inf partial's O holds); -inf in both gives O = 0, LSE = -inf.  o_out / lse_out may
+ * be the same buffers as either input pair (in-place accumulation over the visits).
+ * HYD_BF16 only.  No workspace.
+ */
+hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, const float* lse_b,
+                          int total_tokens, int hq, int head_dim, hyd_dtype dt,
+                          void* o_out, float* lse_out, void* hip_stream);
 
 /*
  * Timing hook for benchmarks: the names and HIP-event durations (milliseconds) of the kernels

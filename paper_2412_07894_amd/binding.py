@@ -15,8 +15,9 @@ _lib = None
 EXPORTS = (
     "hyd_status_string", "hyd_varlen_attn_workspace_bytes", "hyd_varlen_attn_fwd",
     "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
-    "hyd_probe_mfma",
+    "hyd_probe_mfma", "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge",
 )
+RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
 
 class HydError(RuntimeError):
@@ -45,6 +46,13 @@ def load():
     lib.hyd_varlen_attn_bwd.restype = i
     lib.hyd_varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i,
                                         vp, vp, vp, vp, sz, vp]
+    lib.hyd_varlen_attn_fwd_range.restype = i
+    lib.hyd_varlen_attn_fwd_range.argtypes = [vp, vp, vp, ip, i, ip, ip, ip, i, i, i, i, i, f, i, vp, vp, vp, sz, vp]
+    lib.hyd_varlen_attn_bwd_range.restype = i
+    lib.hyd_varlen_attn_bwd_range.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, ip, ip, i, i, i, i, i, f, i,
+                                              vp, vp, vp, vp, sz, vp]
+    lib.hyd_attn_merge.restype = i
+    lib.hyd_attn_merge.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp]
     lib.hyd_enable_kernel_timing.restype = None
     lib.hyd_enable_kernel_timing.argtypes = [i]
     lib.hyd_kernel_times.restype = i
@@ -139,6 +147,76 @@ def varlen_attn_bwd(q, k, v, o, lse, d_o, cu_seqlens, max_seqlen, softmax_scale,
                                    hq, hkv, d, float(softmax_scale), dt, dq.data_ptr(), dk.data_ptr(),
                                    dv.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def _ranges_args(ranges, nseq, device):
+    """ranges: sequence of (q_begin, q_end, kv_begin, kv_end) per sequence -> (device tensor, host
+    array kept alive, host pointer)."""
+    flat = [int(x) for r in ranges for x in r]
+    assert len(flat) == 4 * nseq, "one (q_begin, q_end, kv_begin, kv_end) per sequence"
+    dev = torch.tensor(flat, dtype=torch.int32, device=device) if nseq else torch.zeros(4, dtype=torch.int32, device=device)
+    keep = (ctypes.c_int32 * max(len(flat), 1))(*flat)
+    return dev, keep, ctypes.cast(keep, ctypes.c_void_p)
+
+
+def varlen_attn_fwd_range(q, k, v, cu_seqlens, ranges, max_seqlen, softmax_scale, out, lse,
+                          cu_seqlens_host=None, workspace=None, stream=None):
+    """One visit of a key range to a query range for every sequence (see the header).  `out` and
+    `lse` are caller-owned and only the rows of the query ranges are written."""
+    lib = load()
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    for t in (q, k, v, out, lse, cu_seqlens):
+        assert t.is_contiguous()
+    assert lse.dtype == torch.float32 and lse.shape == (hq, T) and out.shape == q.shape and out.dtype == q.dtype
+    dt = _dtype_code(q)
+    nseq = cu_seqlens.numel() - 1
+    need = workspace_bytes(T, nseq, hq, hkv, d, dt, False)
+    ws = _workspace(need, q.device) if workspace is None else workspace
+    keep, hp = _host_ptr(cu_seqlens_host)
+    rdev, rkeep, rhp = _ranges_args(ranges, nseq, q.device)
+    _check(lib.hyd_varlen_attn_fwd_range(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(), nseq,
+                                         hp, rdev.data_ptr(), rhp, T, int(max_seqlen), hq, hkv, d,
+                                         float(softmax_scale), dt, out.data_ptr(), lse.data_ptr(),
+                                         ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return out, lse
+
+
+def varlen_attn_bwd_range(q, k, v, o, lse, d_o, cu_seqlens, ranges, max_seqlen, softmax_scale, dq, dk, dv,
+                          cu_seqlens_host=None, workspace=None, stream=None):
+    """Partial gradients of one visit; o and lse are the merged forward results.  dq / dk / dv are
+    caller-owned; only the rows of the query (dq) and key (dk, dv) ranges are written."""
+    lib = load()
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    for t in (q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens):
+        assert t.is_contiguous()
+    assert dq.shape == q.shape and dk.shape == k.shape and dv.shape == v.shape
+    dt = _dtype_code(q)
+    nseq = cu_seqlens.numel() - 1
+    need = workspace_bytes(T, nseq, hq, hkv, d, dt, True)
+    ws = _workspace(need, q.device) if workspace is None else workspace
+    keep, hp = _host_ptr(cu_seqlens_host)
+    rdev, rkeep, rhp = _ranges_args(ranges, nseq, q.device)
+    _check(lib.hyd_varlen_attn_bwd_range(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                         d_o.data_ptr(), cu_seqlens.data_ptr(), nseq, hp, rdev.data_ptr(), rhp,
+                                         T, int(max_seqlen), hq, hkv, d, float(softmax_scale), dt,
+                                         dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws.data_ptr(), ws.numel(),
+                                         _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def attn_merge(o_a, lse_a, o_b, lse_b, out=None, lse_out=None, stream=None):
+    """Log-sum-exp merge of two partial results; out / lse_out may be either input pair."""
+    T, hq, d = o_a.shape
+    out = torch.empty_like(o_a) if out is None else out
+    lse_out = torch.empty_like(lse_a) if lse_out is None else lse_out
+    for t in (o_a, lse_a, o_b, lse_b, out, lse_out):
+        assert t.is_contiguous()
+    assert o_b.shape == o_a.shape and lse_a.shape == (hq, T) and lse_b.shape == (hq, T)
+    _check(load().hyd_attn_merge(o_a.data_ptr(), lse_a.data_ptr(), o_b.data_ptr(), lse_b.data_ptr(), T, hq, d,
+                                 _dtype_code(o_a), out.data_ptr(), lse_out.data_ptr(), _stream_ptr(stream)))
+    return out, lse_out
 
 
 def enable_kernel_timing(on):

@@ -10,6 +10,7 @@
 #include "hyd_bwd_bf16.h"
 #include "hyd_fp32.h"
 #include "hyd_fwd_bf16.h"
+#include "hyd_merge.h"
 #include "hyd_probe.h"
 
 namespace {
@@ -103,6 +104,30 @@ hyd_status validate_common(const int32_t* cu, int num_seqs, const int32_t* cu_ho
     return HYD_OK;
 }
 
+// Range variants: begins must fall on the coarsest tile boundary of the three kernels, ends
+// either there or at / past the end of the sequence (then the sequence's length caps them).
+static_assert(HYD_RANGE_ALIGN % kFwdBM == 0 && HYD_RANGE_ALIGN % kDqBM == 0 && HYD_RANGE_ALIGN % kKvBN == 0 &&
+              HYD_RANGE_ALIGN % kFwdBN == 0 && HYD_RANGE_ALIGN % kDqBN == 0 && HYD_RANGE_ALIGN % kKvBM == 0,
+              "range granule must be a multiple of every tile size");
+
+hyd_status validate_ranges(const int32_t* ranges, const int32_t* ranges_host, const int32_t* cu_host,
+                           int num_seqs, int max_seqlen, hyd_dtype dt) {
+    if (dt != HYD_BF16) return HYD_ERR_DTYPE;
+    if (num_seqs == 0) return HYD_OK;
+    if (!ranges) return HYD_ERR_NULL;
+    if (!ranges_host) return HYD_OK;
+    for (int s = 0; s < num_seqs; ++s) {
+        const int32_t* r = ranges_host + 4 * s;
+        const int L = cu_host ? cu_host[s + 1] - cu_host[s] : max_seqlen;
+        for (int e = 0; e < 2; ++e) {
+            const int b = r[2 * e], en = r[2 * e + 1];
+            if (b < 0 || b % HYD_RANGE_ALIGN != 0 || en < b) return HYD_ERR_RANGE;
+            if (en % HYD_RANGE_ALIGN != 0 && en < L) return HYD_ERR_RANGE;
+        }
+    }
+    return HYD_OK;
+}
+
 // ---- per-device state -------------------------------------------------------------------------
 struct DeviceInfo {
     bool ready = false, ok = false;
@@ -132,9 +157,12 @@ hyd_status device_info(DeviceInfo** out) {
         d.ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
         d.cus = prop.multiProcessorCount;
         if (d.ok) {
-            if (!prep_kernel(hyd_fwd_bf16_kernel, kFwdThreads, kFwdLds, &d.occ_fwd) ||
-                !prep_kernel(hyd_bwd_dq_bf16_kernel, kDqThreads, kDqLds, &d.occ_dq) ||
-                !prep_kernel(hyd_bwd_dkdv_bf16_kernel, kKvThreads, kKvLds, &d.occ_kv) ||
+            if (!prep_kernel(hyd_fwd_bf16_kernel<false>, kFwdThreads, kFwdLds, &d.occ_fwd) ||
+                !prep_kernel(hyd_bwd_dq_bf16_kernel<false>, kDqThreads, kDqLds, &d.occ_dq) ||
+                !prep_kernel(hyd_bwd_dkdv_bf16_kernel<false>, kKvThreads, kKvLds, &d.occ_kv) ||
+                !prep_kernel(hyd_fwd_bf16_kernel<true>, kFwdThreads, kFwdLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dq_bf16_kernel<true>, kDqThreads, kDqLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dkdv_bf16_kernel<true>, kKvThreads, kKvLds, nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<64>, kF32Tile, f32_dkdv_lds<64>(), nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<128>, kF32Tile, f32_dkdv_lds<128>(), nullptr))
                 return HYD_ERR_LAUNCH;
@@ -207,6 +235,7 @@ const char* hyd_status_string(hyd_status st) {
         case HYD_ERR_ARCH: return "HYD_ERR_ARCH: device is not gfx950";
         case HYD_ERR_LAUNCH: return "HYD_ERR_LAUNCH: HIP launch or query failed";
         case HYD_ERR_INFEASIBLE: return "HYD_ERR_INFEASIBLE: the planning constraints admit no solution";
+        case HYD_ERR_RANGE: return "HYD_ERR_RANGE: a range begin is not a multiple of HYD_RANGE_ALIGN, or an end is neither that nor past the sequence";
     }
     return "unknown hyd_status";
 }
@@ -218,14 +247,24 @@ size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, i
     return ws_layout(total_tokens, num_seqs, is_bwd ? tile_bwd(dt) : tile_fwd(dt), hq, is_bwd != 0).total;
 }
 
-hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
-                               int num_seqs, const int32_t* cu_seqlens_host, int total_tokens,
-                               int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
-                               hyd_dtype dt, void* o, float* lse, void* workspace,
-                               size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// forward of the plain entry point (ranges == NULL) and of the range variant
+hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                    int num_seqs, const int32_t* cu_seqlens_host, const int32_t* ranges,
+                    const int32_t* ranges_host, bool ranged, int total_tokens,
+                    int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
+                    hyd_dtype dt, void* o, float* lse, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
     const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
                                           hq, hkv, head_dim, dt, workspace, workspace_bytes, false);
     if (vs != HYD_OK) return vs;
+    if (ranged) {
+        const hyd_status rs = validate_ranges(ranges, ranges_host, cu_seqlens_host, num_seqs, max_seqlen, dt);
+        if (rs != HYD_OK) return rs;
+    }
     if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
     if (!q || !k || !v || !o || !lse) return HYD_ERR_NULL;
 
@@ -251,9 +290,11 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
         p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale_log2 = softmax_scale * kLog2e;
         p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
-        KernelTimer kt("fwd_bf16", st);
-        hipLaunchKernelGGL(hyd_fwd_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_fwd, work)),
-                           dim3(kFwdThreads), kFwdLds, st, p);
+        p.ranges = ranged ? ranges : nullptr;
+        const dim3 grid(persistent_grid(*dev, dev->occ_fwd, work));
+        KernelTimer kt(ranged ? "fwd_range_bf16" : "fwd_bf16", st);
+        if (ranged) hipLaunchKernelGGL(hyd_fwd_bf16_kernel<true>, grid, dim3(kFwdThreads), kFwdLds, st, p);
+        else hipLaunchKernelGGL(hyd_fwd_bf16_kernel<false>, grid, dim3(kFwdThreads), kFwdLds, st, p);
     } else {
         F32Params p;
         memset(&p, 0, sizeof(p));
@@ -269,14 +310,20 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
 }
 
-hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
-                               const void* d_o, const int32_t* cu_seqlens, int num_seqs,
-                               const int32_t* cu_seqlens_host, int total_tokens, int max_seqlen, int hq,
-                               int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq, void* dk,
-                               void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+// backward of the plain entry point (ranges == NULL) and of the range variant
+hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                    const void* d_o, const int32_t* cu_seqlens, int num_seqs,
+                    const int32_t* cu_seqlens_host, const int32_t* ranges, const int32_t* ranges_host,
+                    bool ranged, int total_tokens, int max_seqlen, int hq,
+                    int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq, void* dk,
+                    void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
     const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
                                           hq, hkv, head_dim, dt, workspace, workspace_bytes, true);
     if (vs != HYD_OK) return vs;
+    if (ranged) {
+        const hyd_status rs = validate_ranges(ranges, ranges_host, cu_seqlens_host, num_seqs, max_seqlen, dt);
+        if (rs != HYD_OK) return rs;
+    }
     if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
     if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return HYD_ERR_NULL;
 
@@ -314,11 +361,13 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
         p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
         p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
+        p.ranges = ranged ? ranges : nullptr;
         {
             p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
-            KernelTimer kt("bwd_dkdv_bf16", st);
-            hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_kv, work_kv)),
-                               dim3(kKvThreads), kKvLds, st, p);
+            const dim3 grid(persistent_grid(*dev, dev->occ_kv, work_kv));
+            KernelTimer kt(ranged ? "bwd_dkdv_range_bf16" : "bwd_dkdv_bf16", st);
+            if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
+            else hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<false>, grid, dim3(kKvThreads), kKvLds, st, p);
         }
         if (tile_dq(dt) != tile_kv(dt)) {
             KernelTimer kt("schedule_prelude", st);
@@ -326,9 +375,10 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
         }
         {
             p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
-            KernelTimer kt("bwd_dq_bf16", st);
-            hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel, dim3(persistent_grid(*dev, dev->occ_dq, work_q)),
-                               dim3(kDqThreads), kDqLds, st, p);
+            const dim3 grid(persistent_grid(*dev, dev->occ_dq, work_q));
+            KernelTimer kt(ranged ? "bwd_dq_range_bf16" : "bwd_dq_bf16", st);
+            if (ranged) hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<true>, grid, dim3(kDqThreads), kDqLds, st, p);
+            else hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<false>, grid, dim3(kDqThreads), kDqLds, st, p);
         }
     } else {
         F32Params p;
@@ -360,6 +410,76 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
             { KernelTimer kt("bwd_dq_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_dq_fp32_kernel<128>, dim3(grid_q), dim3(kF32Tile), 0, st, p); }
         }
+    }
+    return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                               int num_seqs, const int32_t* cu_seqlens_host, int total_tokens,
+                               int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
+                               hyd_dtype dt, void* o, float* lse, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+    return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false, total_tokens,
+                    max_seqlen, hq, hkv, head_dim, softmax_scale, dt, o, lse, workspace, workspace_bytes,
+                    hip_stream);
+}
+
+hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                               const void* d_o, const int32_t* cu_seqlens, int num_seqs,
+                               const int32_t* cu_seqlens_host, int total_tokens, int max_seqlen, int hq,
+                               int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq, void* dk,
+                               void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bwd_impl(q, k, v, o, lse, d_o, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false,
+                    total_tokens, max_seqlen, hq, hkv, head_dim, softmax_scale, dt, dq, dk, dv, workspace,
+                    workspace_bytes, hip_stream);
+}
+
+hyd_status hyd_varlen_attn_fwd_range(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                                     int num_seqs, const int32_t* cu_seqlens_host, const int32_t* ranges,
+                                     const int32_t* ranges_host, int total_tokens, int max_seqlen, int hq,
+                                     int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* o,
+                                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, ranges, ranges_host, true, total_tokens,
+                    max_seqlen, hq, hkv, head_dim, softmax_scale, dt, o, lse, workspace, workspace_bytes,
+                    hip_stream);
+}
+
+hyd_status hyd_varlen_attn_bwd_range(const void* q, const void* k, const void* v, const void* o,
+                                     const float* lse, const void* d_o, const int32_t* cu_seqlens,
+                                     int num_seqs, const int32_t* cu_seqlens_host, const int32_t* ranges,
+                                     const int32_t* ranges_host, int total_tokens, int max_seqlen, int hq,
+                                     int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq,
+                                     void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+    return bwd_impl(q, k, v, o, lse, d_o, cu_seqlens, num_seqs, cu_seqlens_host, ranges, ranges_host, true,
+                    total_tokens, max_seqlen, hq, hkv, head_dim, softmax_scale, dt, dq, dk, dv, workspace,
+                    workspace_bytes, hip_stream);
+}
+
+hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, const float* lse_b,
+                          int total_tokens, int hq, int head_dim, hyd_dtype dt, void* o_out, float* lse_out,
+                          void* hip_stream) {
+    if (dt != HYD_BF16) return HYD_ERR_DTYPE;
+    if (total_tokens < 0) return HYD_ERR_SHAPE;
+    if (hq <= 0) return HYD_ERR_HEADS;
+    if (!head_dim_ok(dt, head_dim)) return HYD_ERR_HEADDIM;
+    if (total_tokens == 0) return HYD_OK;
+    if (!o_a || !lse_a || !o_b || !lse_b || !o_out || !lse_out) return HYD_ERR_NULL;
+    DeviceInfo* dev = nullptr;
+    const hyd_status ds = device_info(&dev);
+    if (ds != HYD_OK) return ds;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (t_timing) timed_clear();
+    const long long rows = (long long)total_tokens * hq;
+    {
+        KernelTimer kt("merge_bf16", st);
+        hipLaunchKernelGGL(hyd_merge_bf16_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st,
+                           static_cast<const uint16_t*>(o_a), lse_a, static_cast<const uint16_t*>(o_b), lse_b,
+                           static_cast<uint16_t*>(o_out), lse_out, total_tokens, hq);
     }
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
 }

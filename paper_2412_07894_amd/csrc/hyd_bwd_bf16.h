@@ -53,6 +53,7 @@ struct BwdParams {
     const int* hdr; int* cursors; const int* items;
     HeadMap hm;
     WgTrace tr;
+    const int32_t* ranges;            // range variants only: per sequence (q_begin, q_end, kv_begin, kv_end)
 };
 
 // Writes a transposed accumulator set acc[4] (rows = head dim, column = this lane's token) as one
@@ -145,6 +146,9 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     }
 }
 
+// R: range variant (see the forward kernel): query tiles outside the query range are skipped,
+// the tile loop covers the key range only, dQ holds that key range's contribution.
+template <bool R>
 __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kDqStages * kDqStageBytes);
@@ -174,13 +178,33 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
         ++n_done;
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kDqBM;
-        const int kv_end = min(L, q0 + kDqBM);
+        int Lq = L, kb = 0, kcap = L;                     // query rows [.., Lq), keys [kb, kcap)
+        if (R) {
+            const i32x4 rg = *reinterpret_cast<const i32x4*>(p.ranges + 4 * wi.seq);
+            Lq = min(L, rg[1]); kb = max(rg[2], 0); kcap = min(L, rg[3]);
+            if (q0 < rg[0] || q0 >= Lq) {
+                have = wf.next(p.hm, p.cursors, p.items, slot, wi);
+                continue;
+            }
+        }
+        const int kv_end = min(kcap, q0 + kDqBM);
         const int n_kt = (kv_end + kDqBN - 1) / kDqBN;
+        const int t_lo = R ? kb / kDqBN : 0;
         const int g = head / G;
         const int wrow0 = q0 + 32 * wave;
         const int qrow = wrow0 + l32;
-        const bool qvalid = qrow < L;
-        const bool active = wrow0 < L;
+        const bool qvalid = qrow < Lq;
+        const bool active = wrow0 < Lq;
+        if (R && kv_end <= kb) {                          // no key of the range is visible: dQ = 0
+            if (qvalid) {
+                uint16_t* op = p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
+                const u32x2 z = {0u, 0u};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
+            }
+            have = wf.next(p.hm, p.cursors, p.items, slot, wi);
+            continue;
+        }
         const int td = wrow0 / kDqBN;                     // this wave's diagonal (= last) tile
         const int diag_kb = (wrow0 % kDqBN) / 32;         // its diagonal block within that tile
         const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowBytes;
@@ -196,8 +220,8 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_b*)(d + kDqTileBytes), 16, dma_voff, soff, 0, 0);
             }
         };
-        dma_tile(0, 0);
-        if (kDqStages == 3 && n_kt > 1) dma_tile(1, 1);
+        dma_tile(t_lo, 0);
+        if (kDqStages == 3 && t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
         bf16x8 qf[8], dof[8];
         float lse2 = 0.f, Dq = 0.f;
@@ -250,12 +274,12 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             __builtin_amdgcn_s_barrier();
         };
         if (kDqStages == 2) {
-            for (int t = 0; t < n_kt; t += 2) {
+            for (int t = t_lo; t < n_kt; t += 2) {
                 step(std::integral_constant<int, 0>{}, t);
                 if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
             }
         } else {
-            for (int t = 0; t < n_kt; t += 3) {
+            for (int t = t_lo; t < n_kt; t += 3) {
                 step(std::integral_constant<int, 0>{}, t);
                 if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
                 if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kDqStages>{}, t + 2);
@@ -293,6 +317,9 @@ constexpr int kKvPBytes = 64 * 16 * 4;                                // one blo
 constexpr int kKvPOff = kKvStages * kKvStageBytes;                    // P exchange: [pair][2][kKvPBytes]
 constexpr int kKvLds = kKvPOff + kKvPairs * 2 * kKvPBytes + 64;
 
+// R: range variant (see the forward kernel): key tiles outside the key range are skipped, the
+// query tiles run over the query range only, dK / dV hold that query range's contribution.
+template <bool R>
 __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kKvPOff + kKvPairs * 2 * kKvPBytes);
@@ -331,15 +358,25 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         const int lev = wi.lev, g = wi.head, row0 = wi.row0, L = wi.len;
         const int n_tiles = (L + kKvBN - 1) / kKvBN;
         const int j0 = (n_tiles - lev) * kKvBN;               // first key of the item
+        int Lq = L, Lk = L, qb = 0;                           // query rows [qb, Lq), keys [.., Lk)
+        if (R) {
+            const i32x4 rg = *reinterpret_cast<const i32x4*>(p.ranges + 4 * wi.seq);
+            qb = rg[0]; Lq = min(L, rg[1]); Lk = min(L, rg[3]);
+            if (j0 < rg[2] || j0 >= Lk) {                     // the whole key tile is outside the range
+                have = wf.next(p.hm, p.cursors, p.items, slot, wi);
+                continue;
+            }
+        }
         const int wkey0 = j0 + 32 * pair;                     // first key of this wave pair
         const int key = wkey0 + l32;
-        const bool kvalid = key < L;
-        const bool active = wkey0 < L;
-        const int qt_first = j0 / kKvBM;                      // first query tile that sees key j0
-        const int n_qt = (L + kKvBM - 1) / kKvBM - qt_first;
+        const bool kvalid = key < Lk;
+        const bool active = wkey0 < Lk;
+        const int qt_first = max(j0, qb) / kKvBM;             // first query tile that sees key j0
+        const int n_qt = max((Lq + kKvBM - 1) / kKvBM - qt_first, 0);
         const int n_iter = n_qt * G;
-        const uint32_t q_bytes = (uint32_t)(L - 1) * q_stride_b + kRowBytes;
-        const uint32_t stat_bytes = (uint32_t)L * 4;
+        // rows past the query range read as zeros (as rows past the sequence do)
+        const uint32_t q_bytes = (uint32_t)(max(Lq, 1) - 1) * q_stride_b + kRowBytes;
+        const uint32_t stat_bytes = (uint32_t)Lq * 4;
 
         // stage load of iteration `it` = (query head it / n_qt of the group, query tile it % n_qt);
         // every wave issues exactly kDmaPerStage loads, so that a vmcnt wait can tell stages apart
@@ -367,7 +404,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + which * kKvBM * 4),
                                                      4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
         };
-        dma_stage(0, 0);
+        if (n_iter > 0) dma_stage(0, 0);
         if (n_iter > 1) dma_stage(1, 1);
 
         // this wave's register operand of the first product: K rows (role A) or V rows (role B)

@@ -47,6 +47,7 @@ struct FwdParams {
     const int* hdr; int* cursors; const int* items;
     HeadMap hm;
     WgTrace tr;
+    const int32_t* ranges;            // range variant only: per sequence (q_begin, q_end, kv_begin, kv_end)
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -148,6 +149,12 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     l_run += lsum;
 }
 
+// R: range variant.  Each sequence has a query range [q_begin, q_end) and a key range
+// [kv_begin, kv_end) in local positions, the begins multiples of the query tile: query tiles
+// outside the query range are skipped, the tile loop starts at the key range's first tile and
+// stops at its end, and a row that sees no key of the range gets O = 0 and LSE = -inf (the
+// neutral element of the log-sum-exp merge of partial results).
+template <bool R>
 __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_bf16_kernel(FwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kFwdStages * kFwdStageBytes);
@@ -179,13 +186,34 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         ++n_done;
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kFwdBM;
-        const int kv_end = min(L, q0 + kFwdBM);
+        int Lq = L, kb = 0, kcap = L;                     // query rows [.., Lq), keys [kb, kcap)
+        if (R) {
+            const i32x4 rg = *reinterpret_cast<const i32x4*>(p.ranges + 4 * wi.seq);
+            Lq = min(L, rg[1]); kb = max(rg[2], 0); kcap = min(L, rg[3]);
+            if (q0 < rg[0] || q0 >= Lq) {                 // the whole query tile is outside the range
+                have = wf.next(p.hm, p.cursors, p.items, slot, wi);
+                continue;
+            }
+        }
+        const int kv_end = min(kcap, q0 + kFwdBM);
         const int n_kt = (kv_end + kFwdBN - 1) / kFwdBN;
+        const int t_lo = R ? kb / kFwdBN : 0;             // first key tile
         const int g = head / G;
         const int wrow0 = q0 + 32 * wave;                 // first query row of this wave
         const int qrow = wrow0 + l32;
-        const bool qvalid = qrow < L;
-        const bool active = wrow0 < L;                    // else the wave only helps with the loads
+        const bool qvalid = qrow < Lq;
+        const bool active = wrow0 < Lq;                   // else the wave only helps with the loads
+        if (R && kv_end <= kb) {                          // no key of the range is visible to this tile
+            if (qvalid) {
+                uint16_t* op = p.o + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
+                const u32x2 z = {0u, 0u};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
+                if (half == 0) p.lse[(int64_t)head * p.T + row0 + qrow] = -INFINITY;
+            }
+            have = wf.next(p.hm, p.cursors, p.items, slot, wi);
+            continue;
+        }
         const int td = wrow0 / kFwdBN;                    // this wave's diagonal (= last) tile
         const int koff0 = 4 * half - qrow;                // first key slot of the lane minus its query row, tile 0
         // K/V rows [0, kv_end) of this sequence and KV head; reads past them return zero
@@ -202,8 +230,8 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void*)(d + kFwdTileBytes), 16, dma_voff, soff, 0, 0);
             }
         };
-        dma_tile(0, 0);
-        if (kFwdStages == 3 && n_kt > 1) dma_tile(1, 1);
+        dma_tile(t_lo, 0);
+        if (kFwdStages == 3 && t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
         bf16x8 qf[8];
         {
@@ -242,12 +270,12 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             __builtin_amdgcn_s_barrier();
         };
         if (kFwdStages == 2) {
-            for (int t = 0; t < n_kt; t += 2) {
+            for (int t = t_lo; t < n_kt; t += 2) {
                 step(std::integral_constant<int, 0>{}, t);
                 if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kFwdStages>{}, t + 1);
             }
         } else {
-            for (int t = 0; t < n_kt; t += 3) {
+            for (int t = t_lo; t < n_kt; t += 3) {
                 step(std::integral_constant<int, 0>{}, t);
                 if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kFwdStages>{}, t + 1);
                 if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kFwdStages>{}, t + 2);
@@ -255,7 +283,8 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         }
         // epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = l_run + shfl_xor32(l_run);
-        const float inv = 1.f / l_tot;
+        // range variant: a row below the key range has l = 0, m = -inf: O = 0, LSE = -inf
+        const float inv = (R && !(l_tot > 0.f)) ? 0.f : 1.f / l_tot;
         if (qvalid) {
             uint16_t* op = p.o + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
 #pragma unroll

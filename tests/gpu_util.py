@@ -72,3 +72,20 @@ def check(name, got, ref, dtype, report=None):
     assert np.all(np.isfinite(got)), f"{name}: non-finite values"
     assert np.all(err <= tol), line
     assert rel <= tr, line
+
+
+def sample_rows(cu, hq, rng, n_random):
+    """Sampled (token, head) pairs for full-size checks: sequence starts and ends, tile boundaries,
+    the longest and the shortest sequence, plus n_random uniform draws."""
+    lens = np.diff(cu)
+    toks = []
+    longest = int(np.argmax(lens))
+    for s in {0, longest, len(lens) - 1, int(np.argmin(np.where(lens > 0, lens, 1 << 30)))}:
+        a, L = int(cu[s]), int(lens[s])
+        for off in (0, 1, 31, 32, 63, 64, 127, 128, 255, 256, L // 2, L - 2, L - 1):
+            if 0 <= off < L:
+                toks.append(a + off)
+    toks += [int(t) for t in rng.integers(0, int(cu[-1]), n_random)]
+    toks = np.array(sorted(set(toks)), dtype=np.int32)
+    heads = rng.integers(0, hq, len(toks)).astype(np.int32)
+    return toks, heads

@@ -104,10 +104,58 @@ def test_backward_argument_errors(lib):
     assert bwd(T=0, nseq=0, max_len=0, ws=None, ws_bytes=0) == 0
 
 
+def test_range_argument_errors(lib):
+    """Range variants: ranges are checked against the host copies before anything is launched."""
+    RANGE = 11
+
+    def fwd_range(ranges, ranges_dev=1 << 20, cu=(0, 600, 1000), **kw):
+        a = dict(q=1 << 20, k=1 << 20, v=1 << 20, cu=1 << 20, nseq=2, T=1000, max_len=600, hq=4, hkv=2, d=128,
+                 scale=0.1, dt=0, o=1 << 20, lse=1 << 20, ws=1 << 20, ws_bytes=1 << 30, stream=None)
+        a.update(kw)
+        keep_c, pc = host_cu(list(cu)) if cu is not None else (None, None)
+        keep_r, pr = host_cu([x for r in ranges for x in r])
+        return lib.hyd_varlen_attn_fwd_range(a["q"], a["k"], a["v"], a["cu"], a["nseq"], pc, ranges_dev, pr, a["T"],
+                                             a["max_len"], a["hq"], a["hkv"], a["d"], a["scale"], a["dt"], a["o"],
+                                             a["lse"], a["ws"], a["ws_bytes"], a["stream"])
+    good = [(0, 256, 0, 600), (256, 400, 0, 256)]                # ends: aligned, or at / past the sequence's end
+    assert fwd_range(good, q=None) == 1                          # passes the range checks, stops at the NULL q
+    assert fwd_range(good, ranges_dev=None) == 1
+    assert fwd_range(good, dt=1, d=64) == 3                      # bf16 only
+    assert fwd_range([(0, 256, 0, 600), (128, 400, 0, 256)]) == RANGE     # begin off the granule
+    assert fwd_range([(0, 300, 0, 600), (256, 400, 0, 256)]) == RANGE     # end inside the sequence, off the granule
+    assert fwd_range([(0, 256, 512, 256), (256, 400, 0, 256)]) == RANGE   # end < begin
+    assert fwd_range([(-256, 256, 0, 600), (256, 400, 0, 256)]) == RANGE
+    assert fwd_range([(0, 256, 0, 599), (256, 400, 0, 256)]) == RANGE     # 599 < 600 = L
+    assert fwd_range([(0, 256, 0, 599), (256, 400, 0, 256)], cu=None) == RANGE   # judged against max_len = 600
+    assert fwd_range([(0, 256, 256, 256), (512, 512, 0, 0)], q=None) == 1  # empty ranges are allowed
+
+    def bwd_range(ranges, **kw):
+        a = dict(q=1 << 20, dt=0)
+        a.update(kw)
+        keep_c, pc = host_cu([0, 600, 1000])
+        keep_r, pr = host_cu([x for r in ranges for x in r])
+        P = 1 << 20
+        return lib.hyd_varlen_attn_bwd_range(a["q"], P, P, P, P, P, P, 2, pc, P, pr, 1000, 600, 4, 2, 128, 0.1, a["dt"],
+                                             P, P, P, P, 1 << 30, None)
+    assert bwd_range(good, q=None) == 1
+    assert bwd_range([(0, 256, 64, 600), (256, 400, 0, 256)]) == RANGE
+    assert bwd_range(good, dt=1) == 3
+
+
+def test_merge_argument_errors(lib):
+    P = 1 << 20
+    assert lib.hyd_attn_merge(P, P, P, P, 100, 4, 128, 1, P, P, None) == 3      # bf16 only
+    assert lib.hyd_attn_merge(P, P, P, P, -1, 4, 128, 0, P, P, None) == 2
+    assert lib.hyd_attn_merge(P, P, P, P, 100, 0, 128, 0, P, P, None) == 4
+    assert lib.hyd_attn_merge(P, P, P, P, 100, 4, 64, 0, P, P, None) == 5
+    assert lib.hyd_attn_merge(P, P, None, P, 100, 4, 128, 0, P, P, None) == 1
+    assert lib.hyd_attn_merge(None, None, None, None, 0, 4, 128, 0, None, None, None) == 0
+
+
 def test_status_strings(lib):
     from paper_2412_07894_amd import binding as b
-    seen = {b.status_string(c) for c in range(11)}
-    assert len(seen) == 11 and all(s.startswith("HYD_") for s in seen)
+    seen = {b.status_string(c) for c in range(12)}
+    assert len(seen) == 12 and all(s.startswith("HYD_") for s in seen)
     assert "unknown" in b.status_string(99)
 
 

@@ -1,0 +1,39 @@
+"""Host logic of the context-parallel view: chunk bounds obey the rules of the range entry points
+and partition every sequence; the pair count of a visit equals a brute-force count."""
+import numpy as np
+
+from paper_2412_07894_amd import cp_study
+
+
+def test_chunk_ranges_partition_and_alignment():
+    lengths = [1, 255, 256, 257, 1300, 5000, 40]
+    for cp in (1, 2, 3, 4, 8):
+        bounds = cp_study.chunk_ranges(lengths, cp, 256)
+        for L, b in zip(lengths, bounds):
+            assert len(b) == cp and b[0][0] == 0
+            for c, (lo, hi) in enumerate(b):
+                assert lo % 256 == 0 and hi >= lo
+                assert hi % 256 == 0 or hi >= L
+                if c + 1 < cp:
+                    assert b[c + 1][0] == hi                 # contiguous
+            assert b[-1][1] >= L                             # covers the sequence
+            sizes = [max(0, min(hi, L) - lo) for lo, hi in b]
+            assert sum(sizes) == L
+
+
+def test_visit_pairs_against_brute_force():
+    lengths = [700, 257, 1030, 40]
+    for cp in (2, 3):
+        bounds = cp_study.chunk_ranges(lengths, cp, 256)
+        total = 0
+        for r in range(cp):
+            for c in range(cp):
+                want = 0
+                for L, b in zip(lengths, bounds):
+                    i = np.arange(L)[:, None]; j = np.arange(L)[None, :]
+                    m = (j <= i) & (i >= b[r][0]) & (i < b[r][1]) & (j >= b[c][0]) & (j < b[c][1])
+                    want += int(m.sum())
+                got = cp_study.visit_pairs(lengths, bounds, r, c)
+                assert got == want, (cp, r, c)
+                total += got
+        assert total == sum(L * (L + 1) // 2 for L in lengths)

@@ -16,21 +16,6 @@ import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-def sample_rows(cu, hq, rng, n_random):
-    lens = np.diff(cu)
-    toks = []
-    longest = int(np.argmax(lens))
-    for s in {0, longest, len(lens) - 1, int(np.argmin(np.where(lens > 0, lens, 1 << 30)))}:
-        a, L = int(cu[s]), int(lens[s])
-        for off in (0, 1, 31, 32, 63, 64, 127, 128, 255, 256, L // 2, L - 2, L - 1):
-            if 0 <= off < L:
-                toks.append(a + off)
-    toks += [int(t) for t in rng.integers(0, int(cu[-1]), n_random)]
-    toks = np.array(sorted(set(toks)), dtype=np.int32)
-    heads = rng.integers(0, hq, len(toks)).astype(np.int32)
-    return toks, heads
-
-
 def run_config(cid, n_rows=160, col_cases=3):
     cfg = wl.CONFIGS[cid]
     lengths = wl.seqlens(cid)
@@ -52,7 +37,7 @@ def run_config(cid, n_rows=160, col_cases=3):
     for t in (o, lse, dq, dk, dv):
         assert bool(torch.isfinite(t).all())
     rng = np.random.default_rng(100 + cid)
-    toks, heads = sample_rows(cu, cfg.hq, rng, n_rows)
+    toks, heads = gu.sample_rows(cu, cfg.hq, rng, n_rows)
     t0 = time.time()
     ro, rlse, rdq = orc.rows(q, k, v, do, cu, cfg.scale, toks, heads)
     print(f"oracle: {len(toks)} sampled rows in {time.time() - t0:.1f}s", flush=True)
