@@ -78,13 +78,9 @@ def run_gpu(cid, steps, warmup, inputs="randn"):
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     per_kernel = {}
 
-    def step(record):
+    def step():
         binding.varlen_attn_fwd(q, k, v, cu, ml, cfg.scale, workspace=ws_f, out=o, lse=lse)
-        tf = binding.kernel_times() if record else []
         binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, cfg.scale, workspace=ws_b, dq=dq, dk=dk, dv=dv)
-        tb = binding.kernel_times() if record else []
-        for name, ms in tf + tb:
-            per_kernel.setdefault(name, []).append(ms)
 
     # one plain copy kernel of known size (256 MiB read, 256 MiB written), outside the timed
     # region: the reference that scales the HBM counters of a `rocprofv3 --pmc` run of this command
@@ -92,19 +88,23 @@ def run_gpu(cid, steps, warmup, inputs="randn"):
     torch.add(cal, 0.0, out=torch.empty_like(cal))
     del cal
     for _ in range(warmup):
-        step(False)
+        step()
     torch.cuda.synchronize()
-    # timed region: exactly `steps` steps, per-kernel HIP events recorded on the launch stream
+    # timed region: exactly `steps` steps; the library brackets every kernel with HIP events on
+    # the launch stream and only records them: the events are read after the region has ended
     binding.enable_kernel_timing(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        step(True)
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    for name, ms in binding.kernel_times():
+        per_kernel.setdefault(name, []).append(ms)
     binding.enable_kernel_timing(False)
     ms_per_step = (t1 - t0) * 1e3 / steps
     pairs = wl.causal_pairs(lengths)
+    # per launch; the schedule prelude runs twice per step (forward; backward: one launch builds the lists of dK/dV and dQ)
     kernels = {n: sum(x) / len(x) for n, x in per_kernel.items()}
     return cfg, lengths, pairs, ms_per_step, kernels
 

@@ -107,7 +107,7 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v,
  *   d_o              device, [T][Hq][d], same dtype
  *   dq, dk, dv       device, outputs, fully overwritten (no atomics: bitwise reproducible)
  *   workspace        device, >= hyd_varlen_attn_workspace_bytes(..., 1) bytes, 256-byte aligned
- * Three kernels are enqueued after the schedule prelude: D = rowsum(dO*O); dK/dV (one work item
+ * Three kernels are enqueued after the schedule prelude (one launch for both item lists): D = rowsum(dO*O); dK/dV (one work item
  * per (sequence, key tile, KV head), looping over the group's query heads); dQ (one work item
  * per (sequence, query tile, query head)).
  */
@@ -191,12 +191,14 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
                           void* o_out, float* lse_out, void* hip_stream);
 
 /*
- * Timing hook for benchmarks: the names and HIP-event durations (milliseconds) of the kernels
- * the most recent fwd / bwd call on this host thread enqueued.  When enabled (on != 0) each
- * later call brackets every kernel with events on the caller's stream; hyd_kernel_times then
- * synchronises those events and fills up to `cap` entries of names[] (static strings) and ms[],
- * returning the number of kernels recorded (0 when timing is off).  Off by default; when off the
- * entry points enqueue nothing but their kernels.
+ * Timing hook for benchmarks.  While enabled (on != 0), every kernel that a later call of this
+ * library enqueues from this host thread is bracketed with HIP events on the caller's stream and
+ * appended to a per-thread list (at most 8192 launches; further ones are not recorded).  Nothing
+ * is synchronised while recording.  hyd_kernel_times synchronises the recorded events, fills up to
+ * `cap` entries of names[] (static strings) and ms[] (milliseconds) in launch order, empties the
+ * list and returns the number of entries filled (0 when timing is off).  Enabling or disabling
+ * also empties the list.  Off by default; when off the entry points enqueue nothing but their
+ * kernels.
  */
 void hyd_enable_kernel_timing(int on);
 int  hyd_kernel_times(const char** names, float* ms, int cap);

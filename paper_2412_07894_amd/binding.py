@@ -223,8 +223,9 @@ def enable_kernel_timing(on):
     load().hyd_enable_kernel_timing(int(bool(on)))
 
 
-def kernel_times(cap=16):
-    """[(kernel name, milliseconds)] of the most recent fwd or bwd call (timing must be enabled)."""
+def kernel_times(cap=8192):
+    """[(kernel name, milliseconds)] in launch order of every kernel enqueued since timing was
+    enabled or since the previous call of this function; synchronises on them and empties the list."""
     names = (ctypes.c_char_p * cap)()
     ms = (ctypes.c_float * cap)()
     n = load().hyd_kernel_times(names, ms, cap)

@@ -75,12 +75,10 @@ def rank_visits(cid, cp, rank, reps=5, warmup=2):
         per = {}
         for it in range(warmup + reps):
             binding.varlen_attn_fwd_range(q, k, v, cu, ranges, ml, cfg.scale, part_o, part_l, cu_seqlens_host=hc, workspace=ws)
-            t = binding.kernel_times()
             binding.attn_merge(acc_o, acc_l, part_o, part_l, out=acc_o, lse_out=acc_l)
-            t += binding.kernel_times()
             binding.varlen_attn_bwd_range(q, k, v, o_full, lse_full, do, cu, ranges, ml, cfg.scale, dq, dk, dv,
                                           cu_seqlens_host=hc, workspace=ws)
-            t += binding.kernel_times()
+            t = binding.kernel_times()
             if it >= warmup:
                 for name, ms in t:
                     per.setdefault(name, []).append(ms)

@@ -20,24 +20,32 @@ using namespace hyd;
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// Workspace: one or two schedules (the backward has one per tile size when its two kernels use
+// different tiles), then the backward's two float vectors.
+struct SchedLayout { size_t hdr, lev, order, items; int n_lev, max_items; };
 struct WsLayout {
-    size_t hdr, hist, cnt_ge, offs, fill, items, dvec, lse2vec, total;
-    int n_lev, max_items;
+    SchedLayout sched[2];
+    int n_sched;
+    size_t dvec, lse2vec, total;
 };
 
-WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
+size_t sched_layout(SchedLayout& v, size_t at, int T, int nseq, int tile) {
+    v.n_lev = (T + tile - 1) / tile;
+    if (v.n_lev < 1) v.n_lev = 1;
+    v.max_items = T / tile + nseq + 1;
+    v.hdr = at;   at += align_up(sizeof(int) * kHdrInts);
+    v.lev = at;   at += align_up(sizeof(int) * 3 * (size_t)(v.n_lev + 2));
+    v.order = at; at += align_up(sizeof(int) * (size_t)(nseq > 0 ? nseq : 1));
+    v.items = at; at += align_up(sizeof(int) * 4 * (size_t)v.max_items);
+    return at;
+}
+
+WsLayout ws_layout(int T, int nseq, int tile0, int tile1, int hq, bool bwd) {
     WsLayout w;
-    w.n_lev = (T + tile - 1) / tile;
-    if (w.n_lev < 1) w.n_lev = 1;
-    w.max_items = T / tile + nseq + 1;
-    const size_t lev_bytes = align_up(sizeof(int) * (size_t)(w.n_lev + 2));
-    size_t at = 0;
-    w.hdr = at;    at += align_up(sizeof(int) * kHdrInts);
-    w.hist = at;   at += lev_bytes;
-    w.cnt_ge = at; at += lev_bytes;
-    w.offs = at;   at += lev_bytes;
-    w.fill = at;   at += lev_bytes;
-    w.items = at;  at += align_up(sizeof(int) * 4 * (size_t)w.max_items);
+    size_t at = sched_layout(w.sched[0], 0, T, nseq, tile0);
+    w.n_sched = tile1 != tile0 ? 2 : 1;
+    if (w.n_sched == 2) at = sched_layout(w.sched[1], at, T, nseq, tile1);
+    else w.sched[1] = w.sched[0];
     w.dvec = at;
     if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
     w.lse2vec = at;
@@ -50,8 +58,6 @@ WsLayout ws_layout(int T, int nseq, int tile, int hq, bool bwd) {
 int tile_fwd(hyd_dtype dt) { return dt == HYD_BF16 ? kFwdBM : kF32Tile; }
 int tile_dq(hyd_dtype dt) { return dt == HYD_BF16 ? kDqBM : kF32Tile; }
 int tile_kv(hyd_dtype dt) { return dt == HYD_BF16 ? kKvBN : kF32Tile; }
-// the backward workspace is laid out for the smaller of its two tile sizes (more items)
-int tile_bwd(hyd_dtype dt) { return tile_dq(dt) < tile_kv(dt) ? tile_dq(dt) : tile_kv(dt); }
 
 
 bool head_dim_ok(hyd_dtype dt, int d) { return dt == HYD_BF16 ? d == 128 : (d == 64 || d == 128); }
@@ -185,9 +191,11 @@ void timed_clear() {
     t_timed.clear();
 }
 
+constexpr size_t kMaxTimed = 8192;      // launches recorded between two reads of the list
+
 struct KernelTimer {       // brackets one launch with events when timing is on
     hipStream_t st; bool on; TimedKernel tk;
-    KernelTimer(const char* name, hipStream_t s) : st(s), on(t_timing) {
+    KernelTimer(const char* name, hipStream_t s) : st(s), on(t_timing && t_timed.size() < kMaxTimed) {
         tk.name = name;
         if (on) {
             on = hipEventCreate(&tk.e0) == hipSuccess && hipEventCreate(&tk.e1) == hipSuccess;
@@ -199,16 +207,16 @@ struct KernelTimer {       // brackets one launch with events when timing is on
     }
 };
 
-SchedView make_view(char* ws, const WsLayout& w) {
+// View of schedule `which`; its level count is bounded by the caller's max_seqlen.
+SchedView make_view(char* ws, const SchedLayout& v, int tile, int max_seqlen) {
     SchedView sv;
-    sv.hdr = reinterpret_cast<int*>(ws + w.hdr);
-    sv.hist = reinterpret_cast<int*>(ws + w.hist);
-    sv.cnt_ge = reinterpret_cast<int*>(ws + w.cnt_ge);
-    sv.offs = reinterpret_cast<int*>(ws + w.offs);
-    sv.fill = reinterpret_cast<int*>(ws + w.fill);
-    sv.items = reinterpret_cast<int*>(ws + w.items);
-    sv.n_lev = w.n_lev;
-    sv.max_items = w.max_items;
+    sv.hdr = reinterpret_cast<int*>(ws + v.hdr);
+    sv.lev = reinterpret_cast<int*>(ws + v.lev);
+    sv.order = reinterpret_cast<int*>(ws + v.order);
+    sv.items = reinterpret_cast<int*>(ws + v.items);
+    const int by_len = (max_seqlen + tile - 1) / tile;
+    sv.n_lev = by_len < v.n_lev ? (by_len < 1 ? 1 : by_len) : v.n_lev;
+    sv.max_items = v.max_items;
     return sv;
 }
 
@@ -244,7 +252,8 @@ size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, i
                                        hyd_dtype dt, int is_bwd) {
     if (total_tokens < 0 || num_seqs < 0 || hq <= 0 || hkv <= 0 || hq % hkv != 0) return 0;
     if ((dt != HYD_BF16 && dt != HYD_FP32) || !head_dim_ok(dt, head_dim)) return 0;
-    return ws_layout(total_tokens, num_seqs, is_bwd ? tile_bwd(dt) : tile_fwd(dt), hq, is_bwd != 0).total;
+    return (is_bwd ? ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, true)
+                   : ws_layout(total_tokens, num_seqs, tile_fwd(dt), tile_fwd(dt), hq, false)).total;
 }
 
 }  // extern "C"
@@ -272,17 +281,16 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
     const hyd_status ds = device_info(&dev);
     if (ds != HYD_OK) return ds;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (t_timing) timed_clear();
 
     const int tile = tile_fwd(dt);
-    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, hq, false);
-    const SchedView sv = make_view(static_cast<char*>(workspace), w);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, tile, hq, false);
+    const SchedView sv = make_view(static_cast<char*>(workspace), w.sched[0], tile, max_seqlen);
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile, sv);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, tile, sv, tile, sv);
     }
     const HeadMap hm = head_map_q(hq, hkv);
-    const long long work = (long long)w.max_items * hq;
+    const long long work = (long long)sv.max_items * hq;
     if (dt == HYD_BF16) {
         FwdParams p;
         p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
@@ -331,21 +339,22 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     const hyd_status ds = device_info(&dev);
     if (ds != HYD_OK) return ds;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (t_timing) timed_clear();
 
-    const WsLayout w = ws_layout(total_tokens, num_seqs, tile_bwd(dt), hq, true);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, true);
     char* ws = static_cast<char*>(workspace);
-    const SchedView sv = make_view(ws, w);
+    const SchedView sv_kv = make_view(ws, w.sched[0], tile_kv(dt), max_seqlen);
+    const SchedView sv_q = make_view(ws, w.sched[1], tile_dq(dt), max_seqlen);
     float* Dvec = reinterpret_cast<float*>(ws + w.dvec);
     float* Lse2 = reinterpret_cast<float*>(ws + w.lse2vec);
-    // the item list is built for the dK/dV kernel first and, if the dQ kernel uses another tile
-    // size, rebuilt for it once dK/dV has drained (stream order)
+    // one launch builds the item list of the dK/dV kernel and, if the dQ kernel uses another tile
+    // size, the dQ kernel's too (one workgroup each)
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile_kv(dt), sv);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(w.n_sched), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs,
+                           tile_kv(dt), sv_kv, tile_dq(dt), sv_q);
     }
     const long long n_rows = (long long)total_tokens * hq;
-    const long long work_q = (long long)w.max_items * hq, work_kv = (long long)w.max_items * hkv;
+    const long long work_q = (long long)sv_q.max_items * hq, work_kv = (long long)sv_kv.max_items * hkv;
     if (dt == HYD_BF16) {
         {
             KernelTimer kt("bwd_rowdot_bf16", st);
@@ -360,21 +369,19 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
         p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
         p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
-        p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
+        p.tr = t_trace;
         p.ranges = ranged ? ranges : nullptr;
         {
-            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            p.hdr = sv_kv.hdr; p.items = sv_kv.items;
+            p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
             const dim3 grid(persistent_grid(*dev, dev->occ_kv, work_kv));
             KernelTimer kt(ranged ? "bwd_dkdv_range_bf16" : "bwd_dkdv_bf16", st);
             if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
             else hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<false>, grid, dim3(kKvThreads), kKvLds, st, p);
         }
-        if (tile_dq(dt) != tile_kv(dt)) {
-            KernelTimer kt("schedule_prelude", st);
-            hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(1024), 0, st, cu_seqlens, num_seqs, tile_dq(dt), sv);
-        }
         {
-            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            p.hdr = sv_q.hdr; p.items = sv_q.items;
+            p.cursors = sv_q.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
             const dim3 grid(persistent_grid(*dev, dev->occ_dq, work_q));
             KernelTimer kt(ranged ? "bwd_dq_range_bf16" : "bwd_dq_bf16", st);
             if (ranged) hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<true>, grid, dim3(kDqThreads), kDqLds, st, p);
@@ -388,25 +395,25 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
         p.d_o = static_cast<const float*>(d_o); p.lse_in = lse; p.D = Dvec;
         p.dq = static_cast<float*>(dq); p.dk = static_cast<float*>(dk); p.dv = static_cast<float*>(dv);
         p.T = total_tokens; p.hq = hq; p.hkv = hkv; p.scale = softmax_scale;
-        p.hdr = sv.hdr; p.items = sv.items; p.tr = t_trace;
+        p.tr = t_trace;
         const unsigned rd_grid = (unsigned)((n_rows + 255) / 256);
         const int grid_q = persistent_grid(*dev, 8, work_q), grid_kv = persistent_grid(*dev, 2, work_kv);
         if (head_dim == 64) {
             { KernelTimer kt("bwd_rowdot_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_rowdot_fp32_kernel<64>, dim3(rd_grid), dim3(256), 0, st, p.o, p.d_o, Dvec, total_tokens, hq); }
-            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            p.hdr = sv_kv.hdr; p.items = sv_kv.items; p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
             { KernelTimer kt("bwd_dkdv_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_dkdv_fp32_kernel<64>, dim3(grid_kv), dim3(kF32Tile), f32_dkdv_lds<64>(), st, p); }
-            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            p.hdr = sv_q.hdr; p.items = sv_q.items; p.cursors = sv_q.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
             { KernelTimer kt("bwd_dq_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_dq_fp32_kernel<64>, dim3(grid_q), dim3(kF32Tile), 0, st, p); }
         } else {
             { KernelTimer kt("bwd_rowdot_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_rowdot_fp32_kernel<128>, dim3(rd_grid), dim3(256), 0, st, p.o, p.d_o, Dvec, total_tokens, hq); }
-            p.cursors = sv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            p.hdr = sv_kv.hdr; p.items = sv_kv.items; p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
             { KernelTimer kt("bwd_dkdv_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_dkdv_fp32_kernel<128>, dim3(grid_kv), dim3(kF32Tile), f32_dkdv_lds<128>(), st, p); }
-            p.cursors = sv.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
+            p.hdr = sv_q.hdr; p.items = sv_q.items; p.cursors = sv_q.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
             { KernelTimer kt("bwd_dq_fp32", st);
               hipLaunchKernelGGL(hyd_bwd_dq_fp32_kernel<128>, dim3(grid_q), dim3(kF32Tile), 0, st, p); }
         }
@@ -473,7 +480,6 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
     const hyd_status ds = device_info(&dev);
     if (ds != HYD_OK) return ds;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (t_timing) timed_clear();
     const long long rows = (long long)total_tokens * hq;
     {
         KernelTimer kt("merge_bf16", st);
@@ -486,7 +492,7 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
 
 void hyd_enable_kernel_timing(int on) {
     t_timing = on != 0;
-    if (!t_timing) timed_clear();
+    timed_clear();
 }
 
 int hyd_kernel_times(const char** names, float* ms, int cap) {
@@ -499,6 +505,7 @@ int hyd_kernel_times(const char** names, float* ms, int cap) {
         ms[n] = dt;
         ++n;
     }
+    timed_clear();
     return n;
 }
 
@@ -514,7 +521,6 @@ hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_
     const hyd_status st_dev = device_info(&dev);
     if (st_dev != HYD_OK) return st_dev;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    timed_clear();
     {
         KernelTimer kt("probe_mfma", st);
         hipLaunchKernelGGL(hyd_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern);

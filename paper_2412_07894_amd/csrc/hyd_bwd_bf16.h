@@ -378,12 +378,14 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         const uint32_t q_bytes = (uint32_t)(max(Lq, 1) - 1) * q_stride_b + kRowBytes;
         const uint32_t stat_bytes = (uint32_t)Lq * 4;
 
-        // stage load of iteration `it` = (query head it / n_qt of the group, query tile it % n_qt);
+        // stage load of iteration `it` = (query tile it / G, query head it % G of the group): the heads
+        // are the inner loop, so that workgroups on neighbouring key tiles of a sequence move through
+        // its query tiles at the same pace and find some of each other's Q / dO tiles in L2;
         // every wave issues exactly kDmaPerStage loads, so that a vmcnt wait can tell stages apart
         constexpr int kDmaPerStage = 2 * (16 / kKvWaves) + 1;
         auto dma_stage = [&](int it, int stage) {
-            const int h = g * G + it / n_qt;
-            const int qt = qt_first + it % n_qt;
+            const int h = g * G + it % G;
+            const int qt = qt_first + it / G;
             const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * kHeadDim;
             const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + base, q_bytes);
             const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.d_o + base, q_bytes);
@@ -516,7 +518,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             constexpr int ST2 = (ST + 2) % kKvStages;
             constexpr int base = ST * kKvStageBytes;
             const bool more2 = it + 2 < n_iter;
-            const int qt0 = (qt_first + it % n_qt) * kKvBM;
+            const int qt0 = (qt_first + it / G) * kKvBM;
             block(base, 0, 0, qt0);
             // every wave has passed this step's first barrier, hence finished the previous step:
             // the stage that held it may be overwritten now

@@ -25,10 +25,8 @@ constexpr int kHdrCursor = 8;
 
 struct SchedView {            // device pointers into the workspace (all int32)
     int* hdr;                 // kHdrInts
-    int* hist;                // n_lev + 2 : number of sequences with exactly n tiles
-    int* cnt_ge;              // n_lev + 2 : number of sequences with >= c tiles
-    int* offs;                // n_lev + 2 : first list position of level c
-    int* fill;                // n_lev + 2 : scratch counters
+    int* lev;                 // 3 * (n_lev + 2): level arrays, used instead of LDS when n_lev is large
+    int* order;               // n_seq: sequence index by rank (more tiles first, then arrival)
     int* items;               // 4 * max_items : records (s, c, first packed row, length), decreasing c
     int n_lev;                // upper bound on tiles per sequence
     int max_items;
@@ -41,70 +39,87 @@ struct HeadMap {              // how (item, head) pairs are spread over the queu
     int group;                // partitioned: consecutive work indices share group-size heads
 };
 
-// In-place inclusive scan of v[0..n) by one workgroup of NT threads (n arbitrary).
-template <int NT>
-__device__ void block_inclusive_scan(int* v, int n, int* lds /*NT ints*/) {
-    const int tid = threadIdx.x;
-    const int chunk = (n + NT - 1) / NT;
-    const int lo = tid * chunk, hi = min(n, lo + chunk);
+// In-place inclusive scan of v[0..n) by ONE wave (all 64 lanes call it; n arbitrary): every lane
+// sums a contiguous chunk, the chunk sums are scanned across the lanes, each lane rewrites its chunk.
+__device__ __forceinline__ void wave_inclusive_scan(int* v, int n, int lane) {
+    const int chunk = (n + 63) / 64;
+    const int lo = lane * chunk, hi = min(n, lo + chunk);
+    __threadfence_block();                 // v was written by other lanes of this wave
     int sum = 0;
     for (int i = lo; i < hi; ++i) sum += v[i];
-    lds[tid] = sum;
-    __syncthreads();
-    for (int d = 1; d < NT; d <<= 1) {
-        int add = (tid >= d) ? lds[tid - d] : 0;
-        __syncthreads();
-        lds[tid] += add;
-        __syncthreads();
+    int run = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(run, d, 64);
+        if (lane >= d) run += up;
     }
-    int run = lds[tid] - sum;
+    run -= sum;
     for (int i = lo; i < hi; ++i) { run += v[i]; v[i] = run; }
-    __syncthreads();
+    __threadfence_block();                 // and is read by other lanes next
 }
 
-// One workgroup of 1024 threads.  Builds the item list for tile size `tile` and clears the
-// cursors.  Order among items of equal cost is unspecified (it never changes a result: every
-// output element has exactly one producer).
-__global__ void __launch_bounds__(1024) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq,
-                                                             int tile, SchedView sv) {
-    __shared__ int lds[1024];
+constexpr int kPreludeThreads = 1024;
+constexpr int kPreludeLdsLev = 4096;      // levels whose arrays fit the kernel's LDS
+
+// Builds the item list for tile size `tile` and clears the cursors; one workgroup per list
+// (blockIdx.x = 0: tile0 -> sv0, blockIdx.x = 1: tile1 -> sv1), so the two lists of the backward
+// come from one launch.  n_lev* bounds the tiles per sequence (from the caller's max_seqlen).
+// Order among items of equal cost: by sequence rank (arrival order among equals), which is
+// unspecified (it never changes a result: every output element has exactly one producer).
+__global__ void __launch_bounds__(kPreludeThreads) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq,
+                                                                       int tile0, SchedView sv0, int tile1, SchedView sv1) {
+    __shared__ int lds_lev[3 * (kPreludeLdsLev + 2)];
+    const bool second = blockIdx.x != 0;
+    const int tile = second ? tile1 : tile0;
+    const SchedView sv = second ? sv1 : sv0;
     const int tid = threadIdx.x;
     const int nl = sv.n_lev;
-    for (int i = tid; i < nl + 2; i += 1024) { sv.hist[i] = 0; sv.fill[i] = 0; }
-    for (int i = tid; i < kHdrInts; i += 1024) sv.hdr[i] = 0;
+    int* lev = nl <= kPreludeLdsLev ? lds_lev : sv.lev;
+    int* hist = lev;                       // [n]: sequences with exactly n tiles; later the arrival counters
+    int* cnt = lev + (nl + 2);             // [r]: sequences with >= nl - r tiles (levels in reversed order)
+    int* offs = lev + 2 * (nl + 2);        // [r]: list position after level nl - r
+    for (int i = tid; i < nl + 2; i += kPreludeThreads) hist[i] = 0;
+    for (int i = tid; i < kHdrInts; i += kPreludeThreads) sv.hdr[i] = 0;
     __syncthreads();
-    for (int s = tid; s < nseq; s += 1024) {
+    for (int s = tid; s < nseq; s += kPreludeThreads) {
         const int L = cu[s + 1] - cu[s];
         const int n = min((L + tile - 1) / tile, nl);
-        if (n > 0) atomicAdd(&sv.hist[n], 1);
+        if (n > 0) atomicAdd(&hist[n], 1);
     }
     __syncthreads();
-    // cnt_ge[c] = sum_{n >= c} hist[n]; scan in reversed index order r = nl - c (c = nl .. 1)
-    for (int r = tid; r < nl; r += 1024) sv.cnt_ge[r] = sv.hist[nl - r];
+    if (tid < 64) {
+        // cnt[r] = sum_{n >= nl - r} hist[n]; offs = inclusive scan of cnt
+        for (int r = tid; r < nl; r += 64) cnt[r] = hist[nl - r];
+        wave_inclusive_scan(cnt, nl, tid);
+        for (int r = tid; r < nl; r += 64) offs[r] = cnt[r];
+        wave_inclusive_scan(offs, nl, tid);
+    }
     __syncthreads();
-    block_inclusive_scan<1024>(sv.cnt_ge, nl, lds);
-    // offs (reversed order) = exclusive scan of cnt_ge (reversed order)
-    for (int r = tid; r < nl; r += 1024) sv.offs[r] = sv.cnt_ge[r];
+    const int n_items = nl > 0 ? min(offs[nl - 1], sv.max_items) : 0;
+    if (tid == 0) sv.hdr[0] = n_items;
+    for (int i = tid; i < nl + 2; i += kPreludeThreads) hist[i] = 0;
     __syncthreads();
-    block_inclusive_scan<1024>(sv.offs, nl, lds);
-    if (tid == 0) sv.hdr[0] = (nl > 0) ? sv.offs[nl - 1] : 0;       // total number of items
-    // A sequence with n tiles gets rank = (#sequences with more tiles) + arrival order.
-    // Level c (reversed index r = nl - c) starts at offs[r] - cnt_ge[r] and holds the
-    // sequences of rank < cnt_ge[r].
-    for (int s = tid; s < nseq; s += 1024) {
+    // rank of a sequence with n tiles = (#sequences with more tiles) + arrival order among equals
+    for (int s = tid; s < nseq; s += kPreludeThreads) {
         const int L = cu[s + 1] - cu[s];
         const int n = min((L + tile - 1) / tile, nl);
         if (n == 0) continue;
-        const int more = (n < nl) ? sv.cnt_ge[nl - (n + 1)] : 0;
-        const int rank = more + atomicAdd(&sv.fill[n], 1);
-        for (int c = 1; c <= n; ++c) {
-            const int r = nl - c;
-            const int pos = sv.offs[r] - sv.cnt_ge[r] + rank;
-            if (pos < sv.max_items) {
-                sv.items[4 * pos] = s; sv.items[4 * pos + 1] = c;
-                sv.items[4 * pos + 2] = cu[s]; sv.items[4 * pos + 3] = L;
-            }
+        const int more = (n < nl) ? cnt[nl - (n + 1)] : 0;
+        sv.order[more + atomicAdd(&hist[n], 1)] = s;
+    }
+    __syncthreads();
+    // Level c (reversed index r = nl - c) holds the sequences of rank < cnt[r] at the list
+    // positions [offs[r] - cnt[r], offs[r]): one thread per position finds its level by bisection.
+    for (int pos = tid; pos < n_items; pos += kPreludeThreads) {
+        int lo = 0, hi = nl - 1;               // first r with offs[r] > pos
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (offs[mid] > pos) hi = mid; else lo = mid + 1;
         }
+        const int s = sv.order[pos - (offs[lo] - cnt[lo])];
+        const int a = cu[s];
+        int* rec = sv.items + 4 * pos;
+        rec[0] = s; rec[1] = nl - lo; rec[2] = a; rec[3] = cu[s + 1] - a;
     }
 }
 
