@@ -36,7 +36,15 @@ constexpr int kFwdBM = 32 * kFwdWaves, kFwdBN = 64, kFwdThreads = 64 * kFwdWaves
 constexpr int kFwdStages = kFwdWaves == 8 ? 3 : 2;
 constexpr int kFwdTileBytes = kFwdBN * kRowBytes;                 // 16 KB
 constexpr int kFwdStageBytes = 2 * kFwdTileBytes;                 // K tile, then V tile
-constexpr int kFwdLds = kFwdStages * kFwdStageBytes + 64;         // ring + work slot
+// Q staging: the item's 256 Q rows arrive by direct-to-LDS loads (whole rows per instruction, as
+// the K/V tiles do) in four 64-row tiles: two in a region of their own, two in the ring's last
+// stage, which no K/V tile needs before the first step.
+constexpr int kFwdQxOff = kFwdStages * kFwdStageBytes;
+constexpr int kFwdQxBytes = 2 * kFwdTileBytes;
+constexpr int kFwdLds = kFwdQxOff + kFwdQxBytes + 64;                 // ring + Q staging + work slot
+__device__ __forceinline__ constexpr int fwd_q_stage_off(int j) {
+    return j < 2 ? kFwdQxOff + j * kFwdTileBytes : (kFwdStages - 1) * kFwdStageBytes + (j - 2) * kFwdTileBytes;
+}
 constexpr float kRefSlack = 8.f;                                  // log2 units, see "Reference maximum"
 
 struct FwdParams {
@@ -51,6 +59,7 @@ struct FwdParams {
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2_w;
 
 // One 64-key tile for the 32 rows of a wave.  There is ONE body for all tiles (separate bodies for
 // masked and unmasked tiles make the compiler keep the accumulators twice and copy them at every
@@ -157,13 +166,14 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
 template <bool R>
 __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_bf16_kernel(FwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* slot = reinterpret_cast<int*>(smem + kFwdStages * kFwdStageBytes);
+    static_assert(kFwdWaves == 8 && kFwdStages == 3, "the Q staging assumes a 256-row tile and a free third stage");
+    int* slot = reinterpret_cast<int*>(smem + kFwdQxOff + kFwdQxBytes);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
-    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2;
+    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2, q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
 
@@ -173,7 +183,13 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
     // lane i -> row i/16, chunk position i%16), so lane i fetches the chunk that swz() puts there
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff_q = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
     const uint32_t tile_bytes = kFwdBN * kv_stride_b;                 // one K/V tile in global memory
+    // this wave's 32 Q rows inside the staging area, and its private 8 KB of the (free) ring for O
+    const int q_stage = ((wave >> 1) < 2 ? kFwdQxOff + (wave >> 1) * kFwdTileBytes
+                                         : (kFwdStages - 1) * kFwdStageBytes + ((wave >> 1) - 2) * kFwdTileBytes) +
+                        (wave & 1) * 32 * kRowBytes;
+    const uint32_t o_stage = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)(wave * 32 * kRowBytes);   // absolute LDS address
     // scale * s = |scale| * (-s): a negative scale flips the sign bits of the Q fragments instead
     // (and a zero scale becomes a denormal-free epsilon, so that -inf * scale stays -inf)
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
@@ -233,14 +249,17 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         dma_tile(t_lo, 0);
         if (kFwdStages == 3 && t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
-        bf16x8 qf[8];
-        {
-            const uint16_t* qp = p.q + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 8 * half;
+        {   // Q rows q0 .. q0+255 of this head; rows past the query range read as zeros
+            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kFwdBM) - 1) * q_stride_b + kRowBytes;
+            const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim, q_bytes);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (qvalid) v = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
-                qf[ks] = as_bf16x8(v ^ sign_flip);
+            for (int sub = 0; sub < kFwdBM / 64; ++sub) {
+#pragma unroll
+                for (int j = 0; j < 16 / kFwdWaves; ++j) {
+                    char* d = smem + fwd_q_stage_off(sub) + (4 * wave + j * kFwdWaves * 4) * kRowBytes;
+                    const uint32_t soff = (uint32_t)(sub * 64 + j * kFwdWaves * 4) * q_stride_b;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, (lds_void*)d, 16, dma_voff_q, soff, 0, 0);
+                }
             }
         }
         f32x16 acc_o[4];
@@ -249,7 +268,20 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
         float m_ref = -INFINITY, l_run = 0.f;
-        __syncthreads();                                  // waits for tile 0, then the barrier
+        __syncthreads();                                  // the first tiles and the Q rows have landed
+        bf16x8 qf[8];
+        {
+            u32x4 qv[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) qv[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)q_stage);
+            __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                asm volatile("" : "+v"(qv[ks]));          // the reads stay on this side of the barrier
+                qf[ks] = as_bf16x8(qv[ks] ^ sign_flip);
+            }
+        }
+        __builtin_amdgcn_s_barrier();                     // the staged Q may be overwritten (tile t_lo+2 goes there)
 
         // one tile on ring stage ST (compile-time, so that fragment reads are base+immediate)
         auto step = [&](auto stage_tag, int t) {
@@ -285,18 +317,34 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         const float l_tot = l_run + shfl_xor32(l_run);
         // range variant: a row below the key range has l = 0, m = -inf: O = 0, LSE = -inf
         const float inv = (R && !(l_tot > 0.f)) ? 0.f : 1.f / l_tot;
-        if (qvalid) {
-            uint16_t* op = p.o + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
+        if (active) {
+            // O goes through this wave's 8 KB of the ring (free now), so that every store
+            // instruction writes whole 256-byte rows instead of 16 bytes of each of 32 rows.
+            // The lane index is laundered here so that the addresses below are formed after the
+            // tile loop (hoisted above it they would hold some 40 registers through the loop).
+            int le = lane;
+            asm volatile("" : "+v"(le));
+            const int l32e = le & 31, halfe = le >> 5, c16 = le & 15, r4 = le >> 4;
+            const uint32_t wbase = o_stage + (uint32_t)(l32e * kRowBytes + 8 * halfe);
+            const int wswz = swz(l32e);
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     u32x2 w = {pack_bf16(acc_o[db][4 * rq] * inv, acc_o[db][4 * rq + 1] * inv),
                                pack_bf16(acc_o[db][4 * rq + 2] * inv, acc_o[db][4 * rq + 3] * inv)};
-                    *reinterpret_cast<u32x2*>(op + 32 * db + 8 * rq) = w;
+                    *(lds_u32x2_w*)(uintptr_t)(wbase + (uint32_t)(((4 * db + rq) ^ wswz) << 4)) = w;
                 }
             }
-            if (half == 0)
+            // rows 4k + r4 of the wave's block: swz() of such a row is ((r4 & 3) << 2) | (k & 3)
+            uint16_t* ob = p.o + (int64_t)(row0 + wrow0 + r4) * q_stride + (int64_t)head * kHeadDim + 8 * c16;
+            const uint32_t rbase = o_stage + (uint32_t)(r4 * kRowBytes);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const u32x4 w = *(lds_u32x4*)(uintptr_t)(rbase + (uint32_t)(4 * k * kRowBytes + ((c16 ^ (((r4 & 3) << 2) | (k & 3))) << 4)));
+                if (wrow0 + 4 * k + r4 < Lq) *reinterpret_cast<u32x4*>(ob + (int64_t)(4 * k) * q_stride) = w;
+            }
+            if (qvalid && half == 0)
                 p.lse[(int64_t)head * p.T + row0 + qrow] =
                     (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
         }
