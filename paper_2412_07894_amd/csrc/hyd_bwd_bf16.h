@@ -56,20 +56,6 @@ struct BwdParams {
     const int32_t* ranges;            // range variants only: per sequence (q_begin, q_end, kv_begin, kv_end)
 };
 
-// Writes a transposed accumulator set acc[4] (rows = head dim, column = this lane's token) as one
-// bf16 row fragment: lane (l32, half) owns columns 32*db + 8*rq + 4*half + {0..3}.
-__device__ __forceinline__ void store_rows_bf16(uint16_t* row_ptr, const f32x16 (&acc)[4], float mul, int half) {
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            u32x2 w = {pack_bf16(acc[db][4 * rq] * mul, acc[db][4 * rq + 1] * mul),
-                       pack_bf16(acc[db][4 * rq + 2] * mul, acc[db][4 * rq + 3] * mul)};
-            *reinterpret_cast<u32x2*>(row_ptr + 32 * db + 8 * rq + 4 * half) = w;
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // dQ.  Work item = (sequence, query tile of 32*NW rows, query head); wave w owns rows 32w..32w+31.
 // Same orientation, K/V ring and causal structure as the forward kernel: S^T[key][q] = K Q^T and
@@ -85,7 +71,12 @@ constexpr int kDqBM = 32 * kDqWaves, kDqBN = 64, kDqThreads = 64 * kDqWaves;
 constexpr int kDqStages = kDqWaves == 8 ? 3 : 2;
 constexpr int kDqTileBytes = kDqBN * kRowBytes;
 constexpr int kDqStageBytes = 2 * kDqTileBytes;
-constexpr int kDqLds = kDqStages * kDqStageBytes + 64;
+// Staging of the item's Q and dO rows (direct-to-LDS loads of whole rows, as in the forward
+// kernel): Q in a region of its own, dO in ring stages 1 and 2, which no K/V tile needs before
+// the rows have been taken into registers.  The work slot shares the first bytes of the Q region:
+// it is idle while rows are staged (a barrier separates its last read from those loads).
+constexpr int kDqQxOff = kDqStages * kDqStageBytes;
+constexpr int kDqLds = kDqQxOff + kDqBM * kRowBytes;                  // 160 KB: all of a CU's LDS
 
 typedef __attribute__((address_space(3))) void lds_void_b;
 
@@ -150,14 +141,15 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
 // the tile loop covers the key range only, dQ holds that key range's contribution.
 template <bool R>
 __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
+    static_assert(kDqWaves == 8 && kDqStages == 3, "the Q / dO staging assumes a 256-row tile and a 3-stage ring");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* slot = reinterpret_cast<int*>(smem + kDqStages * kDqStageBytes);
+    int* slot = reinterpret_cast<int*>(smem + kDqQxOff);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
     const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
-    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2;
+    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2, q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
 
@@ -165,7 +157,11 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
     fa.init(lane, smem);
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff_q = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
     const uint32_t tile_bytes = kDqBN * kv_stride_b;
+    // this wave's 32 rows inside a staged 256-row block, and its private 8 KB of the ring for dQ
+    const int row_stage = wave * 32 * kRowBytes;
+    const uint32_t o_stage = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)row_stage;
     // scale * s = |scale| * (-s): a negative scale flips the sign bits of the Q fragments, which
     // only the score product reads; a zero scale becomes an epsilon so that -inf * scale = -inf
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
@@ -176,6 +172,7 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
     bool have = wf.first(p.hm, p.hdr, p.cursors, p.items, slot, wi);
     while (have) {
         ++n_done;
+        __syncthreads();                                  // everybody has read the work slot: its bytes may be overwritten
         const int lev = wi.lev, head = wi.head, row0 = wi.row0, L = wi.len;
         const int q0 = (lev - 1) * kDqBM;
         int Lq = L, kb = 0, kcap = L;                     // query rows [.., Lq), keys [kb, kcap)
@@ -221,33 +218,43 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             }
         };
         dma_tile(t_lo, 0);
-        if (kDqStages == 3 && t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
-
-        bf16x8 qf[8], dof[8];
+        {   // rows q0 .. q0+255 of Q and dO of this head; rows past the query range read as zeros
+            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kDqBM) - 1) * q_stride_b + kRowBytes;
+            const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim;
+            dma_rows<kDqWaves>(make_rsrc(p.q + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
+                               kDqBM / 64, q_stride_b, wave, dma_voff_q);
+            dma_rows<kDqWaves>(make_rsrc(p.d_o + off, q_bytes), smem + kDqStageBytes, [](int j) { return j * kDqTileBytes; },
+                               kDqBM / 64, q_stride_b, wave, dma_voff_q);
+        }
         float lse2 = 0.f, Dq = 0.f;
-        {
-            const int64_t off = (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 8 * half;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-                if (qvalid) {
-                    a = *reinterpret_cast<const u32x4*>(p.q + off + 16 * ks);
-                    b = *reinterpret_cast<const u32x4*>(p.d_o + off + 16 * ks);
-                }
-                qf[ks] = as_bf16x8(a ^ sign_flip);
-                dof[ks] = as_bf16x8(b);
-            }
-            if (qvalid) {
-                lse2 = p.lse2[(int64_t)head * p.T + row0 + qrow];
-                Dq = p.D[(int64_t)head * p.T + row0 + qrow];
-            }
+        if (qvalid) {
+            lse2 = p.lse2[(int64_t)head * p.T + row0 + qrow];
+            Dq = p.D[(int64_t)head * p.T + row0 + qrow];
         }
         f32x16 acc[4];
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-        __syncthreads();                                  // waits for tile 0, then the barrier
+        __syncthreads();                                  // tile t_lo and the Q / dO rows have landed
+        bf16x8 qf[8], dof[8];
+        {
+            u32x4 a[8], b[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqQxOff + row_stage));
+                b[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqStageBytes + row_stage));
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                asm volatile("" : "+v"(a[ks]), "+v"(b[ks]));      // the reads stay on this side of the barrier
+                qf[ks] = as_bf16x8(a[ks] ^ sign_flip);
+                dof[ks] = as_bf16x8(b[ks]);
+            }
+        }
+        __builtin_amdgcn_s_barrier();                     // stages 1 and 2 may take K/V tiles now
+        if (t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
         auto step = [&](auto stage_tag, int t) {
             constexpr int ST = decltype(stage_tag)::value;
@@ -285,8 +292,9 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
                 if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kDqStages>{}, t + 2);
             }
         }
-        if (qvalid)
-            store_rows_bf16(p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim, acc, p.scale, half);
+        if (active)         // dQ leaves through this wave's 8 KB of the ring (free now): whole rows per store
+            store_rows_via_lds(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * kHeadDim, q_stride, Lq - wrow0,
+                               acc, p.scale, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 2, t_start, n_done);
@@ -344,6 +352,13 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t dma_voff = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
     const uint32_t tile_bytes = kKvBM * q_stride_b;                   // one Q/dO tile in global memory
+    // K and V rows of the item arrive by direct-to-LDS loads of whole rows (K in ring stage 2, V
+    // in the P exchange area, both idle until the first step) and are taken into registers from
+    // there; dK / dV leave through 8 KB of the (then free) ring per wave
+    const uint32_t kv_stride_b = (uint32_t)kv_stride * 2;
+    const uint32_t dma_voff_kv = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t kv_stage = (role_b ? kKvPOff : 2 * kKvStageBytes) + pair * 32 * kRowBytes - (role_b ? kKvTileBytes : 0);
+    const uint32_t o_stage = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)(wave * 32 * kRowBytes);
     // a negative scale flips the sign bits of the K fragments, which only the score product reads;
     // a zero scale becomes an epsilon so that -inf * scale = -inf
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
@@ -369,7 +384,6 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         }
         const int wkey0 = j0 + 32 * pair;                     // first key of this wave pair
         const int key = wkey0 + l32;
-        const bool kvalid = key < Lk;
         const bool active = wkey0 < Lk;
         const int qt_first = max(j0, qb) / kKvBM;             // first query tile that sees key j0
         const int n_qt = max((Lq + kKvBM - 1) / kKvBM - qt_first, 0);
@@ -409,25 +423,36 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         if (n_iter > 0) dma_stage(0, 0);
         if (n_iter > 1) dma_stage(1, 1);
 
-        // this wave's register operand of the first product: K rows (role A) or V rows (role B)
-        bf16x8 bf[8];
-        {
-            const uint16_t* src = role_b ? p.v : p.k;
-            const uint32_t flip = role_b ? 0u : sign_flip;
-            const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim + 8 * half;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                u32x4 a = {0u, 0u, 0u, 0u};
-                if (kvalid) a = *reinterpret_cast<const u32x4*>(src + off + 16 * ks);
-                bf[ks] = as_bf16x8(a ^ flip);
-            }
+        {   // keys j0 .. j0+127 of K and V of this KV head; rows past the key range read as zeros
+            static_assert(kKvBN == 128 && kKvPairs * 2 * kKvPBytes >= kKvBN * kRowBytes, "K/V staging");
+            const uint32_t k_bytes = (uint32_t)(min(Lk - j0, kKvBN) - 1) * kv_stride_b + kRowBytes;
+            const int64_t off = (int64_t)(row0 + j0) * kv_stride + (int64_t)g * kHeadDim;
+            dma_rows<kKvWaves>(make_rsrc(p.k + off, k_bytes), smem + 2 * kKvStageBytes, [](int j) { return j * kKvTileBytes; },
+                               kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
+            dma_rows<kKvWaves>(make_rsrc(p.v + off, k_bytes), smem + kKvPOff, [](int j) { return j * kKvTileBytes; },
+                               kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
         }
         f32x16 acc[4];                                        // dV^T (role A) or dK^T (role B)
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-        __syncthreads();                                      // stages 0 and 1 have landed
+        __syncthreads();                                      // stages 0 and 1 and the K / V rows have landed
+        // this wave's register operand of the first product: K rows (role A) or V rows (role B)
+        bf16x8 bf[8];
+        {
+            u32x4 a[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + kv_stage);
+            __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0)
+            const uint32_t flip = role_b ? 0u : sign_flip;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                asm volatile("" : "+v"(a[ks]));               // the reads stay on this side of the barrier
+                bf[ks] = as_bf16x8(a[ks] ^ flip);
+            }
+        }
+        __builtin_amdgcn_s_barrier();                         // stage 2 and the P area may be written now
 
         // one 32-row block: rows 32*ib.. of the tile in `base`; `parity` selects the P buffer
         auto block = [&](int base, int ib, int parity, int qt0) {         // base: LDS offset of the stage
@@ -534,11 +559,10 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             if (it + 1 < n_iter) step(std::integral_constant<int, 1>{}, it + 1);
             if (it + 2 < n_iter) step(std::integral_constant<int, 2>{}, it + 2);
         }
-        if (kvalid) {
-            const int64_t off = (int64_t)(row0 + key) * kv_stride + (int64_t)g * kHeadDim;
-            if (role_b) store_rows_bf16(p.dk + off, acc, p.scale, half);
-            else store_rows_bf16(p.dv + off, acc, 1.f, half);
-        }
+        __syncthreads();                                      // every wave is done with the ring
+        if (active)
+            store_rows_via_lds((role_b ? p.dk : p.dv) + (int64_t)(row0 + wkey0) * kv_stride + (int64_t)g * kHeadDim, kv_stride,
+                               Lk - wkey0, acc, role_b ? p.scale : 1.f, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 1, t_start, n_done);

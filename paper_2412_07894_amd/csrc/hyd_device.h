@@ -161,6 +161,61 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+
+// Writes a transposed accumulator set acc[4] (rows = head dim, column = this lane's token: lane
+// (l32, half) owns elements 32*db + 8*rq + 4*half + {0..3} of token l32) as 32 bf16 rows of 256
+// bytes, `row_stride` elements apart, starting at `dst`.  The rows pass through 8 KB of LDS that
+// belong to this wave alone (absolute address `stage`, free of other use), so that every store
+// instruction writes four whole rows instead of 16 bytes of each of 32 rows: the address path of
+// a CU handles a fixed number of cache lines per cycle, and 32 lines per instruction made the
+// epilogue of an item as long as two of its steps.  Rows >= rows_valid are not written.
+// The lane index is laundered through an empty asm statement so that the addresses are formed
+// here (hoisted above the caller's tile loop they would hold some 40 registers through it).
+__device__ __forceinline__ void store_rows_via_lds(uint16_t* dst, int64_t row_stride, int rows_valid,
+                                                   const f32x16 (&acc)[4], float mul, uint32_t stage, int lane) {
+    asm volatile("" : "+v"(lane));
+    const int l32 = lane & 31, half = lane >> 5, c16 = lane & 15, r4 = lane >> 4;
+    const uint32_t wbase = stage + (uint32_t)(l32 * kRowBytes + 8 * half);
+    const int wswz = swz(l32);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            u32x2 w = {pack_bf16(acc[db][4 * rq] * mul, acc[db][4 * rq + 1] * mul),
+                       pack_bf16(acc[db][4 * rq + 2] * mul, acc[db][4 * rq + 3] * mul)};
+            *(lds_u32x2*)(uintptr_t)(wbase + (uint32_t)(((4 * db + rq) ^ wswz) << 4)) = w;
+        }
+    }
+    // rows 4k + r4: swz() of such a row is ((r4 & 3) << 2) | (k & 3)
+    uint16_t* ob = dst + (int64_t)r4 * row_stride + 8 * c16;
+    const uint32_t rbase = stage + (uint32_t)(r4 * kRowBytes);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const u32x4 w = *(lds_u32x4*)(uintptr_t)(rbase + (uint32_t)(4 * k * kRowBytes + ((c16 ^ (((r4 & 3) << 2) | (k & 3))) << 4)));
+        if (4 * k + r4 < rows_valid) *reinterpret_cast<u32x4*>(ob + (int64_t)(4 * k) * row_stride) = w;
+    }
+}
+
+// Direct-to-LDS load of a block of `n64` x 64 rows of 256 bytes (row r of the block at byte r *
+// row_stride_b of the resource) into LDS in the swizzled tile layout, 64-row tile j at lds + off(j).
+// All NW waves of the workgroup call it; each issues n64 * 16 / NW instructions.
+template <int NW, typename OffFn>
+__device__ __forceinline__ void dma_rows(const __amdgpu_buffer_rsrc_t& rs, char* lds, OffFn off, int n64,
+                                         uint32_t row_stride_b, int wave, uint32_t voff) {
+    typedef __attribute__((address_space(3))) void lds_void_t;
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+        if (sub < n64) {
+#pragma unroll
+            for (int j = 0; j < 16 / NW; ++j) {
+                char* d = lds + off(sub) + (4 * wave + j * NW * 4) * kRowBytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)d, 16, voff, (uint32_t)(sub * 64 + j * NW * 4) * row_stride_b, 0, 0);
+            }
+        }
+    }
+}
+
 __device__ __forceinline__ float shfl_xor32(float v) {
     // exchange with the lane 32 away (the other half of the wave)
     return __shfl_xor(v, 32, 64);

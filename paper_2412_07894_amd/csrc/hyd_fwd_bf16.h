@@ -59,7 +59,6 @@ struct FwdParams {
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(3))) u32x2 lds_u32x2_w;
 
 // One 64-key tile for the 32 rows of a wave.  There is ONE body for all tiles (separate bodies for
 // masked and unmasked tiles make the compiler keep the accumulators twice and copy them at every
@@ -318,32 +317,9 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         // range variant: a row below the key range has l = 0, m = -inf: O = 0, LSE = -inf
         const float inv = (R && !(l_tot > 0.f)) ? 0.f : 1.f / l_tot;
         if (active) {
-            // O goes through this wave's 8 KB of the ring (free now), so that every store
-            // instruction writes whole 256-byte rows instead of 16 bytes of each of 32 rows.
-            // The lane index is laundered here so that the addresses below are formed after the
-            // tile loop (hoisted above it they would hold some 40 registers through the loop).
-            int le = lane;
-            asm volatile("" : "+v"(le));
-            const int l32e = le & 31, halfe = le >> 5, c16 = le & 15, r4 = le >> 4;
-            const uint32_t wbase = o_stage + (uint32_t)(l32e * kRowBytes + 8 * halfe);
-            const int wswz = swz(l32e);
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    u32x2 w = {pack_bf16(acc_o[db][4 * rq] * inv, acc_o[db][4 * rq + 1] * inv),
-                               pack_bf16(acc_o[db][4 * rq + 2] * inv, acc_o[db][4 * rq + 3] * inv)};
-                    *(lds_u32x2_w*)(uintptr_t)(wbase + (uint32_t)(((4 * db + rq) ^ wswz) << 4)) = w;
-                }
-            }
-            // rows 4k + r4 of the wave's block: swz() of such a row is ((r4 & 3) << 2) | (k & 3)
-            uint16_t* ob = p.o + (int64_t)(row0 + wrow0 + r4) * q_stride + (int64_t)head * kHeadDim + 8 * c16;
-            const uint32_t rbase = o_stage + (uint32_t)(r4 * kRowBytes);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const u32x4 w = *(lds_u32x4*)(uintptr_t)(rbase + (uint32_t)(4 * k * kRowBytes + ((c16 ^ (((r4 & 3) << 2) | (k & 3))) << 4)));
-                if (wrow0 + 4 * k + r4 < Lq) *reinterpret_cast<u32x4*>(ob + (int64_t)(4 * k) * q_stride) = w;
-            }
+            // O leaves through this wave's 8 KB of the ring (free now): whole rows per store
+            store_rows_via_lds(p.o + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * kHeadDim, q_stride, Lq - wrow0,
+                               acc_o, inv, o_stage, lane);
             if (qvalid && half == 0)
                 p.lse[(int64_t)head * p.T + row0 + qrow] =
                     (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
