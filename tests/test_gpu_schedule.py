@@ -72,3 +72,41 @@ def test_item_count_is_the_triangular_tile_count():
         done = int(r[:, 3].sum())
         want = sum(-(-L // tile) for L in lengths) * heads
         assert done == want, (KERNELS[kid], done, want)
+
+
+def test_level_arrays_in_global_memory_when_max_seqlen_is_a_loose_bound():
+    """A caller may pass max_seqlen = T.  With more than half a million tokens that is more
+    levels than the schedule prelude keeps in LDS, so it works in the workspace instead: same
+    item list, same results (sampled oracle rows and keys)."""
+    from oracle import attn_oracle as orc
+    import gpu_util as gu
+    rng = np.random.default_rng(11)
+    lengths = [int(x) for x in rng.integers(200, 1500, size=1300)]
+    lengths[17] = 5000
+    hq, hkv, d = 2, 1, 128
+    cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 61)
+    T = int(cu[-1])
+    assert T > 4096 * 256, "the case must exceed the level count the prelude holds in LDS, for both tile sizes"
+    print(f"\nloose max_seqlen: T={T} sequences={len(lengths)}", flush=True)
+    scale = 1.0 / np.sqrt(d)
+    qd, kd, vd, dod = (gu.to_dev(x, "bf16") for x in (q, k, v, do))
+    cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
+    o, lse = binding.varlen_attn_fwd(qd, kd, vd, cu_d, T, scale)                 # no host copy either
+    dq, dk, dv = binding.varlen_attn_bwd(qd, kd, vd, o, lse, dod, cu_d, T, scale)
+    o2, lse2 = binding.varlen_attn_fwd(qd, kd, vd, cu_d, max(lengths), scale, cu_seqlens_host=[int(x) for x in cu])
+    dq2, dk2, dv2 = binding.varlen_attn_bwd(qd, kd, vd, o2, lse2, dod, cu_d, max(lengths), scale)
+    torch.cuda.synchronize()
+    for a, b in ((o, o2), (lse, lse2), (dq, dq2), (dk, dk2), (dv, dv2)):
+        assert torch.equal(a, b)               # the bound changes the schedule, never a bit of the result
+    toks, heads = gu.sample_rows(cu, hq, rng, 80)
+    ro, rlse, rdq = orc.rows(q, k, v, do, cu, scale, toks, heads)
+    ti, hi = torch.from_numpy(toks.astype(np.int64)).cuda(), torch.from_numpy(heads.astype(np.int64)).cuda()
+    gu.check("o[rows]", gu.to_np(o[ti, hi]), ro, "bf16")
+    gu.check("lse[rows]", gu.to_np(lse[hi, ti]), rlse, "bf16")
+    gu.check("dq[rows]", gu.to_np(dq[ti, hi]), rdq, "bf16")
+    s = 17
+    cols = np.array([0, 1, 127, 128, 2500, 4998, 4999], dtype=np.int32)
+    rk, rv = orc.cols(q, k, v, do, cu, scale, s, 0, cols)
+    idx = torch.from_numpy((cu[s] + cols).astype(np.int64)).cuda()
+    gu.check("dk[keys]", gu.to_np(dk[idx, 0]), rk, "bf16")
+    gu.check("dv[keys]", gu.to_np(dv[idx, 0]), rv, "bf16")
