@@ -63,12 +63,9 @@ struct BwdParams {
 // dS^T then is the B operand of dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing
 // LDS read of the same K tile.
 // ---------------------------------------------------------------------------------------------
-#ifndef HYD_DQ_WAVES
-#define HYD_DQ_WAVES 8
-#endif
-constexpr int kDqWaves = HYD_DQ_WAVES;
+constexpr int kDqWaves = 8;
 constexpr int kDqBM = 32 * kDqWaves, kDqBN = 64, kDqThreads = 64 * kDqWaves;
-constexpr int kDqStages = kDqWaves == 8 ? 3 : 2;
+constexpr int kDqStages = 3;
 constexpr int kDqTileBytes = kDqBN * kRowBytes;
 constexpr int kDqStageBytes = 2 * kDqTileBytes;
 // Staging of the item's Q and dO rows (direct-to-LDS loads of whole rows, as in the forward
@@ -140,8 +137,8 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
 // R: range variant (see the forward kernel): query tiles outside the query range are skipped,
 // the tile loop covers the key range only, dQ holds that key range's contribution.
 template <bool R>
-__global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_bf16_kernel(BwdParams p) {
-    static_assert(kDqWaves == 8 && kDqStages == 3, "the Q / dO staging assumes a 256-row tile and a 3-stage ring");
+__global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParams p) {
+    static_assert(kDqBM == 256 && kDqStages == 3, "the Q / dO staging assumes a 256-row tile and a 3-stage ring");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kDqQxOff);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -258,15 +255,13 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
 
         auto step = [&](auto stage_tag, int t) {
             constexpr int ST = decltype(stage_tag)::value;
-            constexpr int STN = (ST + 1) % kDqStages;
             constexpr int Kt = ST * kDqStageBytes, Vt = Kt + kDqTileBytes;        // LDS offsets of the tiles
-            // with a 3-stage ring the loads run two tiles ahead: tile t+1 was requested one step
-            // ago and precedes this step's loads in the (in-order) vmcnt queue
+            // the loads run two tiles ahead: tile t+1 was requested one step ago and precedes this
+            // step's loads in the (in-order) vmcnt queue
             constexpr int ST2 = (ST + 2) % kDqStages;
             constexpr int kDmaPerTile = 2 * (16 / kDqWaves);
-            const bool more2 = kDqStages == 3 && t + 2 < n_kt;
-            if (kDqStages == 3) { if (more2) dma_tile(t + 2, ST2); }
-            else if (t + 1 < n_kt) dma_tile(t + 1, STN);
+            const bool more2 = t + 2 < n_kt;
+            if (more2) dma_tile(t + 2, ST2);
             if (active && t <= td) {
                 const bool diag = t == td;
                 // key-minus-row offset of the masked block, formed from the tile index so that the
@@ -280,17 +275,10 @@ __global__ void __launch_bounds__(kDqThreads, kDqWaves == 8 ? 1 : 2) hyd_bwd_dq_
             else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
         };
-        if (kDqStages == 2) {
-            for (int t = t_lo; t < n_kt; t += 2) {
-                step(std::integral_constant<int, 0>{}, t);
-                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
-            }
-        } else {
-            for (int t = t_lo; t < n_kt; t += 3) {
-                step(std::integral_constant<int, 0>{}, t);
-                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kDqStages>{}, t + 1);
-                if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kDqStages>{}, t + 2);
-            }
+        for (int t = t_lo; t < n_kt; t += 3) {
+            step(std::integral_constant<int, 0>{}, t);
+            if (t + 1 < n_kt) step(std::integral_constant<int, 1>{}, t + 1);
+            if (t + 2 < n_kt) step(std::integral_constant<int, 2>{}, t + 2);
         }
         if (active)         // dQ leaves through this wave's 8 KB of the ring (free now): whole rows per store
             store_rows_via_lds(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * kHeadDim, q_stride, Lq - wrow0,

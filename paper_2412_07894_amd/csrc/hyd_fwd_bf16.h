@@ -28,12 +28,9 @@
 
 namespace hyd {
 
-#ifndef HYD_FWD_WAVES
-#define HYD_FWD_WAVES 8
-#endif
-constexpr int kFwdWaves = HYD_FWD_WAVES;
+constexpr int kFwdWaves = 8;
 constexpr int kFwdBM = 32 * kFwdWaves, kFwdBN = 64, kFwdThreads = 64 * kFwdWaves;
-constexpr int kFwdStages = kFwdWaves == 8 ? 3 : 2;
+constexpr int kFwdStages = 3;
 constexpr int kFwdTileBytes = kFwdBN * kRowBytes;                 // 16 KB
 constexpr int kFwdStageBytes = 2 * kFwdTileBytes;                 // K tile, then V tile
 // Q staging: the item's 256 Q rows arrive by direct-to-LDS loads (whole rows per instruction, as
@@ -163,9 +160,9 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
 // stops at its end, and a row that sees no key of the range gets O = 0 and LSE = -inf (the
 // neutral element of the log-sum-exp merge of partial results).
 template <bool R>
-__global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_bf16_kernel(FwdParams p) {
+__global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    static_assert(kFwdWaves == 8 && kFwdStages == 3, "the Q staging assumes a 256-row tile and a free third stage");
+    static_assert(kFwdBM == 256 && kFwdStages == 3, "the Q staging assumes a 256-row tile and a free third stage");
     int* slot = reinterpret_cast<int*>(smem + kFwdQxOff + kFwdQxBytes);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -246,20 +243,12 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
             }
         };
         dma_tile(t_lo, 0);
-        if (kFwdStages == 3 && t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
+        if (t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
         {   // Q rows q0 .. q0+255 of this head; rows past the query range read as zeros
             const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kFwdBM) - 1) * q_stride_b + kRowBytes;
-            const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim, q_bytes);
-#pragma unroll
-            for (int sub = 0; sub < kFwdBM / 64; ++sub) {
-#pragma unroll
-                for (int j = 0; j < 16 / kFwdWaves; ++j) {
-                    char* d = smem + fwd_q_stage_off(sub) + (4 * wave + j * kFwdWaves * 4) * kRowBytes;
-                    const uint32_t soff = (uint32_t)(sub * 64 + j * kFwdWaves * 4) * q_stride_b;
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rq, (lds_void*)d, 16, dma_voff_q, soff, 0, 0);
-                }
-            }
+            dma_rows<kFwdWaves>(make_rsrc(p.q + (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim, q_bytes), smem,
+                                [](int j) { return fwd_q_stage_off(j); }, kFwdBM / 64, q_stride_b, wave, dma_voff_q);
         }
         f32x16 acc_o[4];
 #pragma unroll
@@ -285,32 +274,23 @@ __global__ void __launch_bounds__(kFwdThreads, kFwdWaves == 8 ? 1 : 2) hyd_fwd_b
         // one tile on ring stage ST (compile-time, so that fragment reads are base+immediate)
         auto step = [&](auto stage_tag, int t) {
             constexpr int ST = decltype(stage_tag)::value;
-            constexpr int STN = (ST + 1) % kFwdStages;
             constexpr int Kt = ST * kFwdStageBytes, Vt = Kt + kFwdTileBytes;      // LDS offsets of the tiles
-            // with a 3-stage ring the loads run two tiles ahead: tile t+1 was requested one step
-            // ago and precedes this step's loads in the (in-order) vmcnt queue
+            // the loads run two tiles ahead: tile t+1 was requested one step ago and precedes this
+            // step's loads in the (in-order) vmcnt queue
             constexpr int ST2 = (ST + 2) % kFwdStages;
             constexpr int kDmaPerTile = 2 * (16 / kFwdWaves);
-            const bool more2 = kFwdStages == 3 && t + 2 < n_kt;
-            if (kFwdStages == 3) { if (more2) dma_tile(t + 2, ST2); }
-            else if (t + 1 < n_kt) dma_tile(t + 1, STN);
+            const bool more2 = t + 2 < n_kt;
+            if (more2) dma_tile(t + 2, ST2);
             if (active && t <= td)
                 fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, t * kFwdBN + koff0, t == td);
             if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
             else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
         };
-        if (kFwdStages == 2) {
-            for (int t = t_lo; t < n_kt; t += 2) {
-                step(std::integral_constant<int, 0>{}, t);
-                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kFwdStages>{}, t + 1);
-            }
-        } else {
-            for (int t = t_lo; t < n_kt; t += 3) {
-                step(std::integral_constant<int, 0>{}, t);
-                if (t + 1 < n_kt) step(std::integral_constant<int, 1 % kFwdStages>{}, t + 1);
-                if (t + 2 < n_kt) step(std::integral_constant<int, 2 % kFwdStages>{}, t + 2);
-            }
+        for (int t = t_lo; t < n_kt; t += 3) {
+            step(std::integral_constant<int, 0>{}, t);
+            if (t + 1 < n_kt) step(std::integral_constant<int, 1>{}, t + 1);
+            if (t + 2 < n_kt) step(std::integral_constant<int, 2>{}, t + 2);
         }
         // epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = l_run + shfl_xor32(l_run);
