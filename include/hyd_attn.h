@@ -191,6 +191,27 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
                           void* o_out, float* lse_out, void* hip_stream);
 
 /*
+ * Rotary position embedding of a packed buffer, the position reset at every sequence start
+ * (Sec. 2.1: packing requires that the positional embedding be adjusted so that a sequence keeps
+ * the positions it would have alone; the paper's models, LLaMA 2, use rotary embeddings).  For
+ * packed row t of sequence s, local position m = t - cu_seqlens[s], and pair i in [0, d/2) of
+ * every head:
+ *     angle = m * base^(-2 i / d)
+ *     out[i]       = x[i] cos(angle) - x[i + d/2] sin(angle)
+ *     out[i + d/2] = x[i + d/2] cos(angle) + x[i] sin(angle)
+ * inverse != 0 negates the angle: the transpose of the rotation, which maps the gradient of the
+ * rotated tensor to the gradient of the input.  Apply it to Q and K before the attention calls
+ * and, inverted, to dQ and dK after the backward.
+ *   x, out           device, [T][heads][d] in dt; out may be x (in place)
+ *   cu_seqlens       device int32[num_seqs+1] as above
+ *   base             > 1 (10000 for the paper's models)
+ * HYD_BF16 with head_dim 128 only.  No workspace; one kernel, bound by HBM.
+ */
+hyd_status hyd_rope_packed(const void* x, const int32_t* cu_seqlens, int num_seqs, int total_tokens,
+                           int heads, int head_dim, float base, int inverse, hyd_dtype dt,
+                           void* out, void* hip_stream);
+
+/*
  * Timing hook for benchmarks.  While enabled (on != 0), every kernel that a later call of this
  * library enqueues from this host thread is bracketed with HIP events on the caller's stream and
  * appended to a per-thread list (at most 8192 launches; further ones are not recorded).  Nothing

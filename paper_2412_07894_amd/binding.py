@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "hyd_status_string", "hyd_varlen_attn_workspace_bytes", "hyd_varlen_attn_fwd",
     "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
-    "hyd_probe_mfma", "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge",
+    "hyd_probe_mfma", "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
 )
 RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
@@ -53,6 +53,8 @@ def load():
                                               vp, vp, vp, vp, sz, vp]
     lib.hyd_attn_merge.restype = i
     lib.hyd_attn_merge.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp]
+    lib.hyd_rope_packed.restype = i
+    lib.hyd_rope_packed.argtypes = [vp, ip, i, i, i, i, f, i, i, vp, vp]
     lib.hyd_enable_kernel_timing.restype = None
     lib.hyd_enable_kernel_timing.argtypes = [i]
     lib.hyd_kernel_times.restype = i
@@ -217,6 +219,17 @@ def attn_merge(o_a, lse_a, o_b, lse_b, out=None, lse_out=None, stream=None):
     _check(load().hyd_attn_merge(o_a.data_ptr(), lse_a.data_ptr(), o_b.data_ptr(), lse_b.data_ptr(), T, hq, d,
                                  _dtype_code(o_a), out.data_ptr(), lse_out.data_ptr(), _stream_ptr(stream)))
     return out, lse_out
+
+
+def rope_packed(x, cu_seqlens, base=10000.0, inverse=False, out=None, stream=None):
+    """Rotary embedding with per-sequence position reset on x[T,H,d] (bf16); out may be x."""
+    T, h, d = x.shape
+    out = torch.empty_like(x) if out is None else out
+    assert x.is_contiguous() and out.is_contiguous() and out.shape == x.shape and out.dtype == x.dtype
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
+    _check(load().hyd_rope_packed(x.data_ptr(), cu_seqlens.data_ptr(), cu_seqlens.numel() - 1, T, h, d, float(base),
+                                  int(bool(inverse)), _dtype_code(x), out.data_ptr(), _stream_ptr(stream)))
+    return out
 
 
 def enable_kernel_timing(on):

@@ -3,6 +3,7 @@
 #include "../../include/hyd_attn.h"
 
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <string.h>
 
 #include <vector>
@@ -12,6 +13,7 @@
 #include "hyd_fwd_bf16.h"
 #include "hyd_merge.h"
 #include "hyd_probe.h"
+#include "hyd_rope.h"
 
 namespace {
 
@@ -486,6 +488,27 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
         hipLaunchKernelGGL(hyd_merge_bf16_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st,
                            static_cast<const uint16_t*>(o_a), lse_a, static_cast<const uint16_t*>(o_b), lse_b,
                            static_cast<uint16_t*>(o_out), lse_out, total_tokens, hq);
+    }
+    return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
+}
+
+hyd_status hyd_rope_packed(const void* x, const int32_t* cu_seqlens, int num_seqs, int total_tokens, int heads,
+                           int head_dim, float base, int inverse, hyd_dtype dt, void* out, void* hip_stream) {
+    if (dt != HYD_BF16) return HYD_ERR_DTYPE;
+    if (total_tokens < 0 || num_seqs < 0 || (num_seqs == 0 && total_tokens != 0) || !(base > 1.f)) return HYD_ERR_SHAPE;
+    if (heads <= 0) return HYD_ERR_HEADS;
+    if (!head_dim_ok(dt, head_dim)) return HYD_ERR_HEADDIM;
+    if (total_tokens == 0) return HYD_OK;
+    if (!x || !cu_seqlens || !out) return HYD_ERR_NULL;
+    DeviceInfo* dev = nullptr;
+    const hyd_status ds = device_info(&dev);
+    if (ds != HYD_OK) return ds;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {
+        KernelTimer kt("rope_bf16", st);
+        hipLaunchKernelGGL(hyd_rope_bf16_kernel, dim3((unsigned)((total_tokens + kRopeTok - 1) / kRopeTok)), dim3(kRopeThreads), 0, st,
+                           static_cast<const uint16_t*>(x), cu_seqlens, num_seqs, total_tokens, heads, log2((double)base),
+                           inverse != 0, static_cast<uint16_t*>(out));
     }
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
 }

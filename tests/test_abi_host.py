@@ -152,6 +152,17 @@ def test_merge_argument_errors(lib):
     assert lib.hyd_attn_merge(None, None, None, None, 0, 4, 128, 0, None, None, None) == 0
 
 
+def test_rope_argument_errors(lib):
+    P = 1 << 20
+    f = ctypes.c_float
+    call = lambda **kw: lib.hyd_rope_packed(*[{**dict(x=P, cu=P, nseq=2, T=100, h=4, d=128, base=f(10000.0), inv=0, dt=0, out=P, st=None), **kw}[k]
+                                              for k in ("x", "cu", "nseq", "T", "h", "d", "base", "inv", "dt", "out", "st")])
+    assert call(dt=1) == 3 and call(d=64) == 5 and call(h=0) == 4
+    assert call(T=-1) == 2 and call(nseq=0) == 2 and call(base=f(1.0)) == 2
+    assert call(x=None) == 1 and call(cu=None) == 1 and call(out=None) == 1
+    assert call(T=0, nseq=0, x=None, cu=None, out=None) == 0
+
+
 def test_status_strings(lib):
     from paper_2412_07894_amd import binding as b
     seen = {b.status_string(c) for c in range(12)}
