@@ -37,3 +37,24 @@ def test_visit_pairs_against_brute_force():
                 assert got == want, (cp, r, c)
                 total += got
         assert total == sum(L * (L + 1) // 2 for L in lengths)
+
+
+def test_zigzag_gives_every_rank_the_same_number_of_visible_blocks_and_all_pairs():
+    for lengths, even in (([4096, 8192], True), ([4096, 700, 2049], False)):
+      for cp in (2, 4):
+        seen, counts = 0, []
+        for r in range(cp):
+            visits, n = cp_study.rank_visit_list(cp, r, True)
+            assert n == 2 * cp and len(visits) == 2 * cp + 1
+            bounds = cp_study.chunk_ranges(lengths, n, 256)
+            counts.append(sum(cp_study.visit_pairs(lengths, bounds, a, b) for a, b in visits))
+            seen += counts[-1]
+        assert seen == sum(L * (L + 1) // 2 for L in lengths)          # the ranks together cover every pair once
+        if even:                       # chunks of equal size: every rank holds exactly the same work
+            assert max(counts) == min(counts)
+        plain = []
+        for r in range(cp):
+            visits, n = cp_study.rank_visit_list(cp, r, False)
+            bounds = cp_study.chunk_ranges(lengths, n, 256)
+            plain.append(sum(cp_study.visit_pairs(lengths, bounds, a, b) for a, b in visits))
+        assert sum(plain) == seen and max(plain) / min(plain) > 2.0    # contiguous chunks are not balanced
