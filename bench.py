@@ -99,14 +99,20 @@ def run_gpu(cid, steps, warmup, inputs="randn"):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for name, ms in binding.kernel_times():
+    recorded = binding.kernel_times()
+    for name, ms in recorded:
         per_kernel.setdefault(name, []).append(ms)
     binding.enable_kernel_timing(False)
+    # kernel time of each step (the recorded launches split evenly over the steps): mean, std, min
+    per_step = []
+    if recorded and len(recorded) % steps == 0:
+        n = len(recorded) // steps
+        per_step = [sum(ms for _, ms in recorded[i * n:(i + 1) * n]) for i in range(steps)]
     ms_per_step = (t1 - t0) * 1e3 / steps
     pairs = wl.causal_pairs(lengths)
     # per launch; the schedule prelude runs twice per step (forward; backward: one launch builds the lists of dK/dV and dQ)
     kernels = {n: sum(x) / len(x) for n, x in per_kernel.items()}
-    return cfg, lengths, pairs, ms_per_step, kernels
+    return cfg, lengths, pairs, ms_per_step, kernels, per_step
 
 
 def per_buffer(cid, reps=5, warmup=2):
@@ -191,7 +197,7 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU hot path (no collectives, no sharding); run with --gpus 1")
 
-    cfg, lengths, pairs, ms_per_step, kernels = run_gpu(args.config, args.steps, args.warmup, args.inputs)
+    cfg, lengths, pairs, ms_per_step, kernels, per_step = run_gpu(args.config, args.steps, args.warmup, args.inputs)
     useful = 14.0 * cfg.d * cfg.hq * pairs
     value = useful / (ms_per_step * 1e-3) / 1e12
     out = {
@@ -205,6 +211,10 @@ def main():
                    "head_dim": cfg.d, "causal_pairs": pairs, "useful_flop_per_step": useful},
         "kernel_ms": kernels,
     }
+    if per_step:
+        import statistics
+        out["kernel_ms_per_step"] = {"mean": statistics.fmean(per_step), "std": statistics.pstdev(per_step), "min": min(per_step),
+                                     "what": "sum of the HIP-event durations of one step's kernels (launch gaps excluded)"}
     # dominant kernel: dK/dV.  Algorithmic work = the three products only it provides
     # (dV = P^T dO, dP = dO V^T, dK = dS^T Q): 6 * d * Hq flop per causal pair.
     dom = "bwd_dkdv_bf16" if cfg.dtype == "bf16" else "bwd_dkdv_fp32"
