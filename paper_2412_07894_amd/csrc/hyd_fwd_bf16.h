@@ -1,10 +1,12 @@
 // bf16 forward kernel: block-diagonal causal flash-style tile loop on MFMA with fp32 accumulation.
 //
-// Work item = (sequence, query tile of 32*NW rows, query head).  A workgroup has NW waves; wave w
+// Work item = (sequence, query tile of 256 rows, query head).  A workgroup has 8 waves; wave w
 // owns query rows 32w..32w+31 of the tile for the whole item, so the online softmax never crosses
 // waves.  K/V tiles of 64 keys travel global -> LDS by direct-to-LDS buffer loads (no staging
-// registers, no LDS store instructions) into a ring of stages shared by the NW waves: while tile
-// t is consumed, tile t+1 is in flight.  One barrier per tile.
+// registers, no LDS store instructions) into a ring of three stages shared by the waves: while
+// tile t is consumed, tiles t+1 and t+2 are in flight.  One barrier per tile.  The Q rows of an
+// item come in the same way and are picked up from LDS as fragments; O leaves through LDS too, so
+// that every access to HBM covers whole 256-byte rows.
 //
 // Orientation.  Scores are computed transposed, S^T[key][q] = K Q^T, so that in the accumulator
 // lane map (see mfma32) a lane owns ONE query row (column l%32) and 16 keys per 32-key block:
