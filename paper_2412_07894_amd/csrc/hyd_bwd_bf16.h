@@ -57,7 +57,7 @@ struct BwdParams {
 };
 
 // ---------------------------------------------------------------------------------------------
-// dQ.  Work item = (sequence, query tile of 32*NW rows, query head); wave w owns rows 32w..32w+31.
+// dQ.  Work item = (sequence, query tile of 256 rows, query head); wave w of 8 owns rows 32w..32w+31.
 // Same orientation, K/V ring and causal structure as the forward kernel: S^T[key][q] = K Q^T and
 // dP^T[key][q] = V dO^T put one query row in each lane, so LSE_i and D_i are per-lane scalars;
 // dS^T then is the B operand of dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing
