@@ -15,11 +15,13 @@
  *     (a hipStream_t passed as void*; NULL is the default stream).  Results are valid once the
  *     stream has executed the work enqueued by the call; `workspace` must stay alive until then.
  *   - Layouts are contiguous, token major: Q, O, dO, dQ are [T][Hq][d]; K, V, dK, dV are
- *     [T][Hkv][d]; LSE is float [Hq][T] (natural log).  dtype HYD_BF16: 2-byte bfloat16 elements,
- *     head_dim 128; dtype HYD_FP32: 4-byte float elements, head_dim 64 or 128.  Outputs have the
- *     dtype of the inputs and are fully overwritten.
+ *     [T][Hkv][d]; LSE is float [Hq][T] (natural log).  dtype HYD_BF16: 2-byte bfloat16 elements;
+ *     dtype HYD_FP32: 4-byte float elements; head_dim 64 or 128 for both (the bf16 kernels are
+ *     laid out for 128; at 64 they run the same tiles with half the contraction steps and half
+ *     the output blocks).  Outputs have the dtype of the inputs and are fully overwritten.
  *   - Tiles are fetched through 32-bit buffer resources based at the start of a sequence, so
- *     max_seqlen * Hq * head_dim * element size must be below 4 GiB (HYD_ERR_SHAPE otherwise).
+ *     max_seqlen * Hq * head_dim * element size must be below 4 GiB (2 GiB for bf16 with
+ *     head_dim 64; HYD_ERR_SHAPE otherwise).
  *   - cu_seqlens is int32[num_seqs+1] ON THE DEVICE: cu[0] = 0, cu[num_seqs] = T, non-decreasing;
  *     sequence s owns packed rows [cu[s], cu[s+1]).  Empty sequences are legal.  Every token
  *     belongs to exactly one sequence.  `cu_seqlens_host` is an optional HOST copy of the same
@@ -205,7 +207,7 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
  *   x, out           device, [T][heads][d] in dt; out may be x (in place)
  *   cu_seqlens       device int32[num_seqs+1] as above
  *   base             > 1 (10000 for the paper's models)
- * HYD_BF16 with head_dim 128 only.  No workspace; one kernel, bound by HBM.
+ * HYD_BF16 only (head_dim 64 or 128).  No workspace; one kernel, bound by HBM.
  */
 hyd_status hyd_rope_packed(const void* x, const int32_t* cu_seqlens, int num_seqs, int total_tokens,
                            int heads, int head_dim, float base, int inverse, hyd_dtype dt,

@@ -62,7 +62,7 @@ int tile_dq(hyd_dtype dt) { return dt == HYD_BF16 ? kDqBM : kF32Tile; }
 int tile_kv(hyd_dtype dt) { return dt == HYD_BF16 ? kKvBN : kF32Tile; }
 
 
-bool head_dim_ok(hyd_dtype dt, int d) { return dt == HYD_BF16 ? d == 128 : (d == 64 || d == 128); }
+bool head_dim_ok(hyd_dtype dt, int d) { (void)dt; return d == 64 || d == 128; }
 
 // Spread of (item, head) pairs over the 8 queues: whole KV groups per queue when the KV heads
 // divide over the queues, else single heads, else items striped with all heads in every queue.
@@ -95,7 +95,7 @@ hyd_status validate_common(const int32_t* cu, int num_seqs, const int32_t* cu_ho
     if (max_seqlen > T || max_seqlen < 1) return HYD_ERR_SHAPE;
     // a sequence must fit the 32-bit range of a buffer resource based at its first row
     if ((unsigned long long)max_seqlen * (unsigned long long)hq * (unsigned long long)head_dim *
-            (dt == HYD_BF16 ? 2ull : 4ull) >= (1ull << 32))
+            (dt == HYD_BF16 ? 2ull : 4ull) >= (dt == HYD_BF16 && head_dim == 64 ? (1ull << 31) : (1ull << 32)))
         return HYD_ERR_SHAPE;
     if (cu_host) {
         if (cu_host[0] != 0 || cu_host[num_seqs] != T) return HYD_ERR_SEQLENS;
@@ -166,11 +166,17 @@ hyd_status device_info(DeviceInfo** out) {
         d.cus = prop.multiProcessorCount;
         if (d.ok) {
             if (!prep_kernel(hyd_fwd_bf16_kernel<false>, kFwdThreads, kFwdLds, &d.occ_fwd) ||
+                !prep_kernel(hyd_fwd_bf16_kernel<false, 64>, kFwdThreads, kFwdLds, nullptr) ||
+                !prep_kernel(hyd_fwd_bf16_kernel<true, 64>, kFwdThreads, kFwdLds, nullptr) ||
                 !prep_kernel(hyd_bwd_dq_bf16_kernel<false>, kDqThreads, kDqLds, &d.occ_dq) ||
                 !prep_kernel(hyd_bwd_dkdv_bf16_kernel<false>, kKvThreads, kKvLds, &d.occ_kv) ||
                 !prep_kernel(hyd_fwd_bf16_kernel<true>, kFwdThreads, kFwdLds, nullptr) ||
                 !prep_kernel(hyd_bwd_dq_bf16_kernel<true>, kDqThreads, kDqLds, nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_bf16_kernel<true>, kKvThreads, kKvLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dq_bf16_kernel<false, 64>, kDqThreads, kDqLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dkdv_bf16_kernel<false, 64>, kKvThreads, kKvLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dq_bf16_kernel<true, 64>, kDqThreads, kDqLds, nullptr) ||
+                !prep_kernel(hyd_bwd_dkdv_bf16_kernel<true, 64>, kKvThreads, kKvLds, nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<64>, kF32Tile, f32_dkdv_lds<64>(), nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<128>, kF32Tile, f32_dkdv_lds<128>(), nullptr))
                 return HYD_ERR_LAUNCH;
@@ -303,7 +309,10 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
         p.ranges = ranged ? ranges : nullptr;
         const dim3 grid(persistent_grid(*dev, dev->occ_fwd, work));
         KernelTimer kt(ranged ? "fwd_range_bf16" : "fwd_bf16", st);
-        if (ranged) hipLaunchKernelGGL(hyd_fwd_bf16_kernel<true>, grid, dim3(kFwdThreads), kFwdLds, st, p);
+        if (head_dim == 64) {
+            if (ranged) hipLaunchKernelGGL((hyd_fwd_bf16_kernel<true, 64>), grid, dim3(kFwdThreads), kFwdLds, st, p);
+            else hipLaunchKernelGGL((hyd_fwd_bf16_kernel<false, 64>), grid, dim3(kFwdThreads), kFwdLds, st, p);
+        } else if (ranged) hipLaunchKernelGGL(hyd_fwd_bf16_kernel<true>, grid, dim3(kFwdThreads), kFwdLds, st, p);
         else hipLaunchKernelGGL(hyd_fwd_bf16_kernel<false>, grid, dim3(kFwdThreads), kFwdLds, st, p);
     } else {
         F32Params p;
@@ -360,9 +369,13 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     if (dt == HYD_BF16) {
         {
             KernelTimer kt("bwd_rowdot_bf16", st);
-            hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st,
-                               static_cast<const uint16_t*>(o), static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2,
-                               total_tokens, hq);
+            const dim3 rgrid((unsigned)((n_rows + 15) / 16));
+            if (head_dim == 64)
+                hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2, total_tokens, hq);
+            else
+                hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2, total_tokens, hq);
         }
         BwdParams p;
         p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
@@ -378,7 +391,10 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
             p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
             const dim3 grid(persistent_grid(*dev, dev->occ_kv, work_kv));
             KernelTimer kt(ranged ? "bwd_dkdv_range_bf16" : "bwd_dkdv_bf16", st);
-            if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
+            if (head_dim == 64) {
+                if (ranged) hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<true, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
+                else hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<false, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
+            } else if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
             else hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<false>, grid, dim3(kKvThreads), kKvLds, st, p);
         }
         {
@@ -386,7 +402,10 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
             p.cursors = sv_q.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
             const dim3 grid(persistent_grid(*dev, dev->occ_dq, work_q));
             KernelTimer kt(ranged ? "bwd_dq_range_bf16" : "bwd_dq_bf16", st);
-            if (ranged) hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<true>, grid, dim3(kDqThreads), kDqLds, st, p);
+            if (head_dim == 64) {
+                if (ranged) hipLaunchKernelGGL((hyd_bwd_dq_bf16_kernel<true, 64>), grid, dim3(kDqThreads), kDqLds, st, p);
+                else hipLaunchKernelGGL((hyd_bwd_dq_bf16_kernel<false, 64>), grid, dim3(kDqThreads), kDqLds, st, p);
+            } else if (ranged) hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<true>, grid, dim3(kDqThreads), kDqLds, st, p);
             else hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<false>, grid, dim3(kDqThreads), kDqLds, st, p);
         }
     } else {
@@ -485,9 +504,13 @@ hyd_status hyd_attn_merge(const void* o_a, const float* lse_a, const void* o_b, 
     const long long rows = (long long)total_tokens * hq;
     {
         KernelTimer kt("merge_bf16", st);
-        hipLaunchKernelGGL(hyd_merge_bf16_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st,
-                           static_cast<const uint16_t*>(o_a), lse_a, static_cast<const uint16_t*>(o_b), lse_b,
-                           static_cast<uint16_t*>(o_out), lse_out, total_tokens, hq);
+        const dim3 mgrid((unsigned)((rows + 15) / 16));
+        if (head_dim == 64)
+            hipLaunchKernelGGL(hyd_merge_bf16_kernel<64>, mgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o_a), lse_a,
+                               static_cast<const uint16_t*>(o_b), lse_b, static_cast<uint16_t*>(o_out), lse_out, total_tokens, hq);
+        else
+            hipLaunchKernelGGL(hyd_merge_bf16_kernel<kHeadDim>, mgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o_a), lse_a,
+                               static_cast<const uint16_t*>(o_b), lse_b, static_cast<uint16_t*>(o_out), lse_out, total_tokens, hq);
     }
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
 }
@@ -506,9 +529,13 @@ hyd_status hyd_rope_packed(const void* x, const int32_t* cu_seqlens, int num_seq
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     {
         KernelTimer kt("rope_bf16", st);
-        hipLaunchKernelGGL(hyd_rope_bf16_kernel, dim3((unsigned)((total_tokens + kRopeTok - 1) / kRopeTok)), dim3(kRopeThreads), 0, st,
-                           static_cast<const uint16_t*>(x), cu_seqlens, num_seqs, total_tokens, heads, log2((double)base),
-                           inverse != 0, static_cast<uint16_t*>(out));
+        const dim3 rgrid((unsigned)((total_tokens + kRopeTok - 1) / kRopeTok));
+        if (head_dim == 64)
+            hipLaunchKernelGGL(hyd_rope_bf16_kernel<64>, rgrid, dim3(kRopeThreads), 0, st, static_cast<const uint16_t*>(x), cu_seqlens,
+                               num_seqs, total_tokens, heads, log2((double)base), inverse != 0, static_cast<uint16_t*>(out));
+        else
+            hipLaunchKernelGGL(hyd_rope_bf16_kernel<kHeadDim>, rgrid, dim3(kRopeThreads), 0, st, static_cast<const uint16_t*>(x), cu_seqlens,
+                               num_seqs, total_tokens, heads, log2((double)base), inverse != 0, static_cast<uint16_t*>(out));
     }
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
 }

@@ -18,6 +18,7 @@ namespace hyd {
 // ---------------------------------------------------------------------------------------------
 constexpr float kLog2e = 1.44269504088896340736f;
 
+template <int HD = kHeadDim>
 __global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t* __restrict__ o,
                                                                  const uint16_t* __restrict__ d_o,
                                                                  const float* __restrict__ lse,
@@ -27,9 +28,9 @@ __global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
     float acc = 0.f;
-    if (row < n_rows) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * kHeadDim + c * 8);
-        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + row * kHeadDim + c * 8);
+    if (row < n_rows && (HD == kHeadDim || c < HD / 8)) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + c * 8);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + row * HD + c * 8);
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
     }
@@ -80,25 +81,28 @@ typedef __attribute__((address_space(3))) void lds_void_b;
 // One 32-key block (rows 32*kb.. of the K and V tiles) for the 32 rows of a wave.  `k0`: key index
 // minus row index of the block's first key for this lane's row if the block needs masking, else a
 // value that masks nothing.
+// D: head dimension (128 or 64).
+template <int D>
 __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int kb,
-                                         const bf16x8 (&qf)[8], const bf16x8 (&dof)[8], f32x16 (&acc)[4],
+                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], f32x16 (&acc)[D / 32],
                                          float scale_log2, float lse2, float Dq, bool mask, int krel) {
+    constexpr int NK = D / 16, NDB = D / 32;
     // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
     {
-        // fragment i < 8: K, contraction step i; i >= 8: V, step i - 8; reads run kAhead ahead
+        // fragment i < NK: K, contraction step i; i >= NK: V, step i - NK; reads run kAhead ahead
         constexpr int kAhead = 6;
         bf16x8 f[kAhead];
 #pragma unroll
-        for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < 8 ? Kt : Vt, fa, kb, i & 7);
+        for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < NK ? Kt : Vt, fa, kb, i % NK);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if (i < 8) s = mfma32(f[i % kAhead], qf[i], s);
-            else dp = mfma32(f[i % kAhead], dof[i - 8], dp);
-            if (i + kAhead < 16) f[i % kAhead] = frag_row(i + kAhead < 8 ? Kt : Vt, fa, kb, (i + kAhead) & 7);
+        for (int i = 0; i < 2 * NK; ++i) {
+            if (i < NK) s = mfma32(f[i % kAhead], qf[i], s);
+            else dp = mfma32(f[i % kAhead], dof[i - NK], dp);
+            if (i + kAhead < 2 * NK) f[i % kAhead] = frag_row(i + kAhead < NK ? Kt : Vt, fa, kb, (i + kAhead) % NK);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -106,7 +110,7 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     LdsQueue lq{0};
     ColFrag cf[kCAhead];                      // K^T fragments for the dQ product, requested early
 #pragma unroll
-    for (int i = 0; i < kCAhead; ++i) issue_col(lq, cf[i], Kt, fa, 2 * kb + (i >> 2), i & 3);
+    for (int i = 0; i < kCAhead && i < 2 * NDB; ++i) issue_col(lq, cf[i], Kt, fa, 2 * kb + i / NDB, i % NDB);
     __builtin_amdgcn_sched_barrier(0);
     if (mask) {                               // hidden keys: P = exp2(-inf) = 0
 #pragma unroll
@@ -124,20 +128,25 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     for (int e = 0; e < 4; ++e) dcur[e] = ds_pair(e);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {             // i = 4*b2 + db
-        const int b2 = i >> 2, db = i & 3;
+    for (int i = 0; i < 2 * NDB; ++i) {       // i = NDB*b2 + db
+        const int b2 = i / NDB, db = i % NDB;
         acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(dcur), acc[db]);
-        if (i + kCAhead < 8) issue_col(lq, cf[i % kCAhead], Kt, fa, 2 * kb + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
-        if (b2 == 0) dnxt[db] = ds_pair(4 + db);
+        if (i + kCAhead < 2 * NDB) issue_col(lq, cf[i % kCAhead], Kt, fa, 2 * kb + (i + kCAhead) / NDB, (i + kCAhead) % NDB);
+        if (b2 == 0) {
+#pragma unroll
+            for (int e = 0; e < 4 / NDB; ++e) dnxt[(4 / NDB) * db + e] = ds_pair(4 + (4 / NDB) * db + e);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        if (i == 3) dcur = dnxt;
+        if (i == NDB - 1) dcur = dnxt;
     }
 }
 
 // R: range variant (see the forward kernel): query tiles outside the query range are skipped,
 // the tile loop covers the key range only, dQ holds that key range's contribution.
-template <bool R>
+template <bool R, int D = kHeadDim>
 __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParams p) {
+    static_assert(D == 128 || D == 64, "head dimension");
+    constexpr int kRowB = D * 2;                                      // bytes of a row in global memory
     static_assert(kDqBM == 256 && kDqStages == 3, "the Q / dO staging assumes a 256-row tile and a 3-stage ring");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kDqQxOff);
@@ -145,7 +154,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
-    const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const int64_t q_stride = (int64_t)p.hq * D, kv_stride = (int64_t)p.hkv * D;
     const uint32_t kv_stride_b = (uint32_t)kv_stride * 2, q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
@@ -153,8 +162,8 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
     FragAddr fa;
     fa.init(lane, smem);
     const int dma_row = 4 * wave + (lane >> 4);
-    const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
-    const uint32_t dma_voff_q = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff = dma_lane_voff<D>(dma_row, lane, kv_stride_b);
+    const uint32_t dma_voff_q = dma_lane_voff<D>(dma_row, lane, q_stride_b);
     const uint32_t tile_bytes = kDqBN * kv_stride_b;
     // this wave's 32 rows inside a staged 256-row block, and its private 8 KB of the ring for dQ
     const int row_stage = wave * 32 * kRowBytes;
@@ -191,19 +200,19 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         const bool active = wrow0 < Lq;
         if (R && kv_end <= kb) {                          // no key of the range is visible: dQ = 0
             if (qvalid) {
-                uint16_t* op = p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
+                uint16_t* op = p.dq + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * D + 4 * half;
                 const u32x2 z = {0u, 0u};
 #pragma unroll
-                for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
+                for (int i = 0; i < D / 8; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
             }
             have = wf.next(p.hm, p.cursors, p.items, slot, wi);
             continue;
         }
         const int td = wrow0 / kDqBN;                     // this wave's diagonal (= last) tile
         const int diag_kb = (wrow0 % kDqBN) / 32;         // its diagonal block within that tile
-        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowBytes;
-        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
-        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
+        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowB;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
         auto dma_tile = [&](int t, int stage) {
             char* dst = smem + stage * kDqStageBytes + 4 * wave * kRowBytes;
 #pragma unroll
@@ -216,8 +225,8 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         };
         dma_tile(t_lo, 0);
         {   // rows q0 .. q0+255 of Q and dO of this head; rows past the query range read as zeros
-            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kDqBM) - 1) * q_stride_b + kRowBytes;
-            const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim;
+            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kDqBM) - 1) * q_stride_b + kRowB;
+            const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * D;
             dma_rows<kDqWaves>(make_rsrc(p.q + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
                                kDqBM / 64, q_stride_b, wave, dma_voff_q);
             dma_rows<kDqWaves>(make_rsrc(p.d_o + off, q_bytes), smem + kDqStageBytes, [](int j) { return j * kDqTileBytes; },
@@ -228,23 +237,23 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
             lse2 = p.lse2[(int64_t)head * p.T + row0 + qrow];
             Dq = p.D[(int64_t)head * p.T + row0 + qrow];
         }
-        f32x16 acc[4];
+        f32x16 acc[D / 32];
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
         __syncthreads();                                  // tile t_lo and the Q / dO rows have landed
-        bf16x8 qf[8], dof[8];
+        bf16x8 qf[D / 16], dof[D / 16];
         {
-            u32x4 a[8], b[8];
+            u32x4 a[D / 16], b[D / 16];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < D / 16; ++ks) {
                 a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqQxOff + row_stage));
                 b[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqStageBytes + row_stage));
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < D / 16; ++ks) {
                 asm volatile("" : "+v"(a[ks]), "+v"(b[ks]));      // the reads stay on this side of the barrier
                 qf[ks] = as_bf16x8(a[ks] ^ sign_flip);
                 dof[ks] = as_bf16x8(b[ks]);
@@ -267,9 +276,9 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
                 // key-minus-row offset of the masked block, formed from the tile index so that the
                 // mask comparisons are not hoisted out of the tile loop into scalar registers
                 const int krel = t * kDqBN + 32 * diag_kb + 4 * half - qrow;
-                dq_block(Kt, Vt, fa, 0, qf, dof, acc, scale_log2, lse2, Dq, diag && diag_kb == 0, krel);
+                dq_block<D>(Kt, Vt, fa, 0, qf, dof, acc, scale_log2, lse2, Dq, diag && diag_kb == 0, krel);
                 if (!(diag && diag_kb == 0))
-                    dq_block(Kt, Vt, fa, 1, qf, dof, acc, scale_log2, lse2, Dq, diag, krel);
+                    dq_block<D>(Kt, Vt, fa, 1, qf, dof, acc, scale_log2, lse2, Dq, diag, krel);
             }
             if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
             else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
@@ -281,7 +290,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
             if (t + 2 < n_kt) step(std::integral_constant<int, 2>{}, t + 2);
         }
         if (active)         // dQ leaves through this wave's 8 KB of the ring (free now): whole rows per store
-            store_rows_via_lds(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * kHeadDim, q_stride, Lq - wrow0,
+            store_rows_via_lds<D>(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * D, q_stride, Lq - wrow0,
                                acc, p.scale, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
@@ -315,8 +324,11 @@ constexpr int kKvLds = kKvPOff + kKvPairs * 2 * kKvPBytes + 64;
 
 // R: range variant (see the forward kernel): key tiles outside the key range are skipped, the
 // query tiles run over the query range only, dK / dV hold that query range's contribution.
-template <bool R>
+template <bool R, int D = kHeadDim>
 __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdParams p) {
+    static_assert(D == 128 || D == 64, "head dimension");
+    constexpr int kRowB = D * 2;                                      // bytes of a row in global memory
+    constexpr int NK = D / 16, NDB = D / 32;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int* slot = reinterpret_cast<int*>(smem + kKvPOff + kKvPairs * 2 * kKvPBytes);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -325,7 +337,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     const bool role_b = wave >= kKvPairs;
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
-    const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const int64_t q_stride = (int64_t)p.hq * D, kv_stride = (int64_t)p.hkv * D;
     const uint32_t q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
@@ -338,13 +350,13 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         fa.col[i] += role_b ? 0 : kKvTileBytes;
     }
     const int dma_row = 4 * wave + (lane >> 4);
-    const uint32_t dma_voff = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff = dma_lane_voff<D>(dma_row, lane, q_stride_b);
     const uint32_t tile_bytes = kKvBM * q_stride_b;                   // one Q/dO tile in global memory
     // K and V rows of the item arrive by direct-to-LDS loads of whole rows (K in ring stage 2, V
     // in the P exchange area, both idle until the first step) and are taken into registers from
     // there; dK / dV leave through 8 KB of the (then free) ring per wave
     const uint32_t kv_stride_b = (uint32_t)kv_stride * 2;
-    const uint32_t dma_voff_kv = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff_kv = dma_lane_voff<D>(dma_row, lane, kv_stride_b);
     const uint32_t kv_stage = (role_b ? kKvPOff : 2 * kKvStageBytes) + pair * 32 * kRowBytes - (role_b ? kKvTileBytes : 0);
     const uint32_t o_stage = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)(wave * 32 * kRowBytes);
     // a negative scale flips the sign bits of the K fragments, which only the score product reads;
@@ -377,7 +389,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         const int n_qt = max((Lq + kKvBM - 1) / kKvBM - qt_first, 0);
         const int n_iter = n_qt * G;
         // rows past the query range read as zeros (as rows past the sequence do)
-        const uint32_t q_bytes = (uint32_t)(max(Lq, 1) - 1) * q_stride_b + kRowBytes;
+        const uint32_t q_bytes = (uint32_t)(max(Lq, 1) - 1) * q_stride_b + kRowB;
         const uint32_t stat_bytes = (uint32_t)Lq * 4;
 
         // stage load of iteration `it` = (query tile it / G, query head it % G of the group): the heads
@@ -388,7 +400,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         auto dma_stage = [&](int it, int stage) {
             const int h = g * G + it % G;
             const int qt = qt_first + it / G;
-            const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * kHeadDim;
+            const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * D;
             const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + base, q_bytes);
             const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.d_o + base, q_bytes);
             char* dst = smem + stage * kKvStageBytes + 4 * wave * kRowBytes;
@@ -413,29 +425,29 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 
         {   // keys j0 .. j0+127 of K and V of this KV head; rows past the key range read as zeros
             static_assert(kKvBN == 128 && kKvPairs * 2 * kKvPBytes >= kKvBN * kRowBytes, "K/V staging");
-            const uint32_t k_bytes = (uint32_t)(min(Lk - j0, kKvBN) - 1) * kv_stride_b + kRowBytes;
-            const int64_t off = (int64_t)(row0 + j0) * kv_stride + (int64_t)g * kHeadDim;
+            const uint32_t k_bytes = (uint32_t)(min(Lk - j0, kKvBN) - 1) * kv_stride_b + kRowB;
+            const int64_t off = (int64_t)(row0 + j0) * kv_stride + (int64_t)g * D;
             dma_rows<kKvWaves>(make_rsrc(p.k + off, k_bytes), smem + 2 * kKvStageBytes, [](int j) { return j * kKvTileBytes; },
                                kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
             dma_rows<kKvWaves>(make_rsrc(p.v + off, k_bytes), smem + kKvPOff, [](int j) { return j * kKvTileBytes; },
                                kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
         }
-        f32x16 acc[4];                                        // dV^T (role A) or dK^T (role B)
+        f32x16 acc[NDB];                                      // dV^T (role A) or dK^T (role B)
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
         __syncthreads();                                      // stages 0 and 1 and the K / V rows have landed
         // this wave's register operand of the first product: K rows (role A) or V rows (role B)
-        bf16x8 bf[8];
+        bf16x8 bf[NK];
         {
-            u32x4 a[8];
+            u32x4 a[NK];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + kv_stage);
+            for (int ks = 0; ks < NK; ++ks) a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + kv_stage);
             __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0)
             const uint32_t flip = role_b ? 0u : sign_flip;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < NK; ++ks) {
                 asm volatile("" : "+v"(a[ks]));               // the reads stay on this side of the barrier
                 bf[ks] = as_bf16x8(a[ks] ^ flip);
             }
@@ -458,15 +470,15 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             if (work) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) x[r] = 0.f;
-                constexpr int kAhead = 6;
+                constexpr int kAhead = NK < 6 ? NK : 6;
                 bf16x8 f[kAhead];
 #pragma unroll
                 for (int i = 0; i < kAhead; ++i) f[i] = frag_row(T1, fa, ib, i);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
+                for (int i = 0; i < NK; ++i) {
                     x = mfma32(f[i % kAhead], bf[i], x);
-                    if (i + kAhead < 8) f[i % kAhead] = frag_row(T1, fa, ib, i + kAhead);
+                    if (i + kAhead < NK) f[i % kAhead] = frag_row(T1, fa, ib, i + kAhead);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (!role_b) {
@@ -494,7 +506,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 // these 2 * kCAhead reads are outstanding, the P stores issued before them are done.
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < kCAhead; ++i) issue_col(lq, cf[i], T2, fa, 2 * ib + (i >> 2), i & 3);
+                for (int i = 0; i < kCAhead; ++i) issue_col(lq, cf[i], T2, fa, 2 * ib + i / NDB, i % NDB);
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_waitcnt(0xc07f | ((2 * kCAhead) << 8));
             } else {
@@ -517,11 +529,11 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 for (int i = 0; i < kCAhead; ++i) cf[i].seq = 2 * (i + 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {                 // i = 4*b2 + db
-                    const int b2 = i >> 2, db = i & 3;
+                for (int i = 0; i < 2 * NDB; ++i) {           // i = NDB*b2 + db
+                    const int b2 = i / NDB, db = i % NDB;
                     u32x4 bv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
                     acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(bv), acc[db]);
-                    if (i + kCAhead < 8) issue_col(lq, cf[i % kCAhead], T2, fa, 2 * ib + ((i + kCAhead) >> 2), (i + kCAhead) & 3);
+                    if (i + kCAhead < 2 * NDB) issue_col(lq, cf[i % kCAhead], T2, fa, 2 * ib + (i + kCAhead) / NDB, (i + kCAhead) % NDB);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -549,7 +561,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         }
         __syncthreads();                                      // every wave is done with the ring
         if (active)
-            store_rows_via_lds((role_b ? p.dk : p.dv) + (int64_t)(row0 + wkey0) * kv_stride + (int64_t)g * kHeadDim, kv_stride,
+            store_rows_via_lds<D>((role_b ? p.dk : p.dv) + (int64_t)(row0 + wkey0) * kv_stride + (int64_t)g * D, kv_stride,
                                Lk - wkey0, acc, role_b ? p.scale : 1.f, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }

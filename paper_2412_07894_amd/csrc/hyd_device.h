@@ -172,14 +172,15 @@ typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
 // epilogue of an item as long as two of its steps.  Rows >= rows_valid are not written.
 // The lane index is laundered through an empty asm statement so that the addresses are formed
 // here (hoisted above the caller's tile loop they would hold some 40 registers through it).
+template <int D = kHeadDim>
 __device__ __forceinline__ void store_rows_via_lds(uint16_t* dst, int64_t row_stride, int rows_valid,
-                                                   const f32x16 (&acc)[4], float mul, uint32_t stage, int lane) {
+                                                   const f32x16 (&acc)[D / 32], float mul, uint32_t stage, int lane) {
     asm volatile("" : "+v"(lane));
     const int l32 = lane & 31, half = lane >> 5, c16 = lane & 15, r4 = lane >> 4;
     const uint32_t wbase = stage + (uint32_t)(l32 * kRowBytes + 8 * half);
     const int wswz = swz(l32);
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
+    for (int db = 0; db < D / 32; ++db) {
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
             u32x2 w = {pack_bf16(acc[db][4 * rq] * mul, acc[db][4 * rq + 1] * mul),
@@ -193,8 +194,20 @@ __device__ __forceinline__ void store_rows_via_lds(uint16_t* dst, int64_t row_st
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const u32x4 w = *(lds_u32x4*)(uintptr_t)(rbase + (uint32_t)(4 * k * kRowBytes + ((c16 ^ (((r4 & 3) << 2) | (k & 3))) << 4)));
-        if (4 * k + r4 < rows_valid) *reinterpret_cast<u32x4*>(ob + (int64_t)(4 * k) * row_stride) = w;
+        if (4 * k + r4 < rows_valid && (D == kHeadDim || c16 < D / 8)) *reinterpret_cast<u32x4*>(ob + (int64_t)(4 * k) * row_stride) = w;
     }
+}
+
+// Per-lane byte offset of a direct-to-LDS row load: lane i of a 64-lane instruction fills LDS
+// position i%16 of tile row `row`, which in the swizzled layout holds chunk (i%16) ^ swz(row) of
+// the row.  A head dimension of 64 has only chunks 0..7: the other lanes point far outside the
+// buffer resource (their LDS bytes become zeros; nothing reads them), which requires resources
+// below 2 GiB for D = 64.
+constexpr uint32_t kDmaOutOfRange = 0x7fffff00u;
+template <int D>
+__device__ __forceinline__ uint32_t dma_lane_voff(int row, int lane, uint32_t row_stride_b) {
+    const int chunk = (lane & 15) ^ swz(row);
+    return (D == kHeadDim || chunk < D / 8) ? (uint32_t)row * row_stride_b + (uint32_t)(chunk << 4) : kDmaOutOfRange;
 }
 
 // Direct-to-LDS load of a block of `n64` x 64 rows of 256 bytes (row r of the block at byte r *

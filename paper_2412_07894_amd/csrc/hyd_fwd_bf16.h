@@ -63,9 +63,12 @@ typedef __attribute__((address_space(3))) void lds_void;
 // masked and unmasked tiles make the compiler keep the accumulators twice and copy them at every
 // join); only the masking itself sits in a wave-uniform branch.  `diag`: this is the wave's
 // diagonal tile (its second 32-key block may be hidden altogether).
-__device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, const bf16x8 (&qf)[8],
-                                         f32x16 (&acc_o)[4], float& m_ref, float& l_run, float scale_log2,
+// D: head dimension (128 or 64): D/16 contraction steps in the score product, D/32 output blocks.
+template <int D>
+__device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, const bf16x8 (&qf)[D / 16],
+                                         f32x16 (&acc_o)[D / 32], float& m_ref, float& l_run, float scale_log2,
                                          int koff, bool diag) {
+    constexpr int NK = D / 16, NDB = D / 32;
     // The instruction order below is pinned with scheduling fences: left alone, the compiler sinks
     // every LDS read next to its use and serialises read -> wait -> MFMA.
     f32x16 s[2];
@@ -81,9 +84,9 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
         for (int i = 0; i < kAhead; ++i) kf[i] = frag_row(Kt, fa, i & 1, i >> 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 2 * NK; ++i) {
             s[i & 1] = mfma32(kf[i % kAhead], qf[i >> 1], s[i & 1]);
-            if (i + kAhead < 16) kf[i % kAhead] = frag_row(Kt, fa, (i + kAhead) & 1, (i + kAhead) >> 1);
+            if (i + kAhead < 2 * NK) kf[i % kAhead] = frag_row(Kt, fa, (i + kAhead) & 1, (i + kAhead) >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -92,7 +95,7 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     LdsQueue lq{0};
     ColFrag vf[kVAhead];
 #pragma unroll
-    for (int i = 0; i < kVAhead; ++i) issue_col(lq, vf[i], Vt, fa, i >> 2, i & 3);
+    for (int i = 0; i < kVAhead; ++i) issue_col(lq, vf[i], Vt, fa, i / NDB, i % NDB);
     __builtin_amdgcn_sched_barrier(0);
     if (diag) {         // hidden keys score -inf (scale_log2 > 0 always, so exp2 turns them into 0)
         // koff = position of the tile's first key slot of this lane minus the lane's query row.
@@ -120,13 +123,13 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
         const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
         l_run *= alpha;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
         m_ref = m_new;
     }
-    // P V: the exponentials of key step b+1 (8 scores) issue under the 4 MFMAs of step b, two
-    // scores per MFMA; V fragments are read kVAhead MFMAs ahead.
+    // P V: the exponentials of key step b+1 (8 scores) issue under the NDB MFMAs of step b (two
+    // scores per MFMA for D = 128, four for D = 64); V fragments are read kVAhead MFMAs ahead.
     float lsum = 0.f;
     auto exp_pair = [&](int j) -> uint32_t {           // scores 2j, 2j+1 of the 32 a lane holds
         const int kb = j >> 3, r = (2 * j) & 15;
@@ -145,13 +148,16 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     for (int e = 0; e < 4; ++e) pcur[e] = exp_pair(e);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {                      // i = 4*b + db
-        const int b = i >> 2, db = i & 3;
+    for (int i = 0; i < 4 * NDB; ++i) {                 // i = NDB*b + db
+        const int b = i / NDB, db = i % NDB;
         acc_o[db] = mfma32(lds_wait(lq, vf[i % kVAhead]), as_bf16x8(pcur), acc_o[db]);
-        if (i + kVAhead < 16) issue_col(lq, vf[i % kVAhead], Vt, fa, (i + kVAhead) >> 2, (i + kVAhead) & 3);
-        if (b < 3) pnxt[db] = exp_pair(4 * (b + 1) + db);
+        if (i + kVAhead < 4 * NDB) issue_col(lq, vf[i % kVAhead], Vt, fa, (i + kVAhead) / NDB, (i + kVAhead) % NDB);
+        if (b < 3) {
+#pragma unroll
+            for (int e = 0; e < 4 / NDB; ++e) pnxt[(4 / NDB) * db + e] = exp_pair(4 * (b + 1) + (4 / NDB) * db + e);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        if (db == 3) pcur = pnxt;
+        if (db == NDB - 1) pcur = pnxt;
     }
     l_run += lsum;
 }
@@ -161,8 +167,10 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
 // outside the query range are skipped, the tile loop starts at the key range's first tile and
 // stops at its end, and a row that sees no key of the range gets O = 0 and LSE = -inf (the
 // neutral element of the log-sum-exp merge of partial results).
-template <bool R>
+template <bool R, int D = kHeadDim>
 __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams p) {
+    static_assert(D == 128 || D == 64, "head dimension");
+    constexpr int kRowB = D * 2;                                      // bytes of a row in global memory
     extern __shared__ __attribute__((aligned(16))) char smem[];
     static_assert(kFwdBM == 256 && kFwdStages == 3, "the Q staging assumes a 256-row tile and a free third stage");
     int* slot = reinterpret_cast<int*>(smem + kFwdQxOff + kFwdQxBytes);
@@ -170,7 +178,7 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int G = p.hq / p.hkv;
-    const int64_t q_stride = (int64_t)p.hq * kHeadDim, kv_stride = (int64_t)p.hkv * kHeadDim;
+    const int64_t q_stride = (int64_t)p.hq * D, kv_stride = (int64_t)p.hkv * D;
     const uint32_t kv_stride_b = (uint32_t)kv_stride * 2, q_stride_b = (uint32_t)q_stride * 2;
     const unsigned long long t_start = p.tr.rec ? wall_clock64() : 0ull;
     unsigned long long n_done = 0;
@@ -180,8 +188,8 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
     // direct-to-LDS tile load: instruction j of wave w fills tile rows 4*(j*NW + w) .. +3 (1 KB,
     // lane i -> row i/16, chunk position i%16), so lane i fetches the chunk that swz() puts there
     const int dma_row = 4 * wave + (lane >> 4);
-    const uint32_t dma_voff = (uint32_t)dma_row * kv_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
-    const uint32_t dma_voff_q = (uint32_t)dma_row * q_stride_b + (uint32_t)(((lane & 15) ^ swz(dma_row)) << 4);
+    const uint32_t dma_voff = dma_lane_voff<D>(dma_row, lane, kv_stride_b);
+    const uint32_t dma_voff_q = dma_lane_voff<D>(dma_row, lane, q_stride_b);
     const uint32_t tile_bytes = kFwdBN * kv_stride_b;                 // one K/V tile in global memory
     // this wave's 32 Q rows inside the staging area, and its private 8 KB of the (free) ring for O
     const int q_stage = ((wave >> 1) < 2 ? kFwdQxOff + (wave >> 1) * kFwdTileBytes
@@ -219,10 +227,10 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
         const bool active = wrow0 < Lq;                   // else the wave only helps with the loads
         if (R && kv_end <= kb) {                          // no key of the range is visible to this tile
             if (qvalid) {
-                uint16_t* op = p.o + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * kHeadDim + 4 * half;
+                uint16_t* op = p.o + (int64_t)(row0 + qrow) * q_stride + (int64_t)head * D + 4 * half;
                 const u32x2 z = {0u, 0u};
 #pragma unroll
-                for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
+                for (int i = 0; i < D / 8; ++i) *reinterpret_cast<u32x2*>(op + 8 * i) = z;
                 if (half == 0) p.lse[(int64_t)head * p.T + row0 + qrow] = -INFINITY;
             }
             have = wf.next(p.hm, p.cursors, p.items, slot, wi);
@@ -231,9 +239,9 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
         const int td = wrow0 / kFwdBN;                    // this wave's diagonal (= last) tile
         const int koff0 = 4 * half - qrow;                // first key slot of the lane minus its query row, tile 0
         // K/V rows [0, kv_end) of this sequence and KV head; reads past them return zero
-        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowBytes;
-        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
-        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * kHeadDim, kv_bytes);
+        const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowB;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
         auto dma_tile = [&](int t, int stage) {
             char* dst = smem + stage * kFwdStageBytes + 4 * wave * kRowBytes;
 #pragma unroll
@@ -248,25 +256,25 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
         if (t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
 
         {   // Q rows q0 .. q0+255 of this head; rows past the query range read as zeros
-            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kFwdBM) - 1) * q_stride_b + kRowBytes;
-            dma_rows<kFwdWaves>(make_rsrc(p.q + (int64_t)(row0 + q0) * q_stride + (int64_t)head * kHeadDim, q_bytes), smem,
+            const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kFwdBM) - 1) * q_stride_b + kRowB;
+            dma_rows<kFwdWaves>(make_rsrc(p.q + (int64_t)(row0 + q0) * q_stride + (int64_t)head * D, q_bytes), smem,
                                 [](int j) { return fwd_q_stage_off(j); }, kFwdBM / 64, q_stride_b, wave, dma_voff_q);
         }
-        f32x16 acc_o[4];
+        f32x16 acc_o[D / 32];
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
         float m_ref = -INFINITY, l_run = 0.f;
         __syncthreads();                                  // the first tiles and the Q rows have landed
-        bf16x8 qf[8];
+        bf16x8 qf[D / 16];
         {
-            u32x4 qv[8];
+            u32x4 qv[D / 16];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) qv[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)q_stage);
+            for (int ks = 0; ks < D / 16; ++ks) qv[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + (uint32_t)q_stage);
             __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < D / 16; ++ks) {
                 asm volatile("" : "+v"(qv[ks]));          // the reads stay on this side of the barrier
                 qf[ks] = as_bf16x8(qv[ks] ^ sign_flip);
             }
@@ -284,7 +292,7 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
             const bool more2 = t + 2 < n_kt;
             if (more2) dma_tile(t + 2, ST2);
             if (active && t <= td)
-                fwd_tile(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, t * kFwdBN + koff0, t == td);
+                fwd_tile<D>(Kt, Vt, fa, qf, acc_o, m_ref, l_run, scale_log2, t * kFwdBN + koff0, t == td);
             if (more2) __builtin_amdgcn_s_waitcnt(0x0070 | (kDmaPerTile & 15));     // vmcnt(kDmaPerTile), lgkmcnt(0)
             else __builtin_amdgcn_s_waitcnt(0x0070);                                // vmcnt(0), lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
@@ -300,7 +308,7 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
         const float inv = (R && !(l_tot > 0.f)) ? 0.f : 1.f / l_tot;
         if (active) {
             // O leaves through this wave's 8 KB of the ring (free now): whole rows per store
-            store_rows_via_lds(p.o + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * kHeadDim, q_stride, Lq - wrow0,
+            store_rows_via_lds<D>(p.o + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * D, q_stride, Lq - wrow0,
                                acc_o, inv, o_stage, lane);
             if (qvalid && half == 0)
                 p.lse[(int64_t)head * p.T + row0 + qrow] =

@@ -10,13 +10,14 @@
 namespace hyd {
 
 // o_out / lse_out may alias either input (each lane reads what it overwrites before writing it).
+template <int D = kHeadDim>
 __global__ void __launch_bounds__(256) hyd_merge_bf16_kernel(const uint16_t* o_a, const float* lse_a,
                                                             const uint16_t* o_b, const float* lse_b,
                                                             uint16_t* o_out, float* lse_out, int T, int hq) {
     const int64_t n_rows = (int64_t)T * hq;
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
-    if (row >= n_rows) return;
+    if (row >= n_rows || (D != kHeadDim && c >= D / 8)) return;
     const int t = (int)(row / hq), h = (int)(row % hq);
     const int64_t si = (int64_t)h * T + t;
     const float la = lse_a[si], lb = lse_b[si];
@@ -30,8 +31,8 @@ __global__ void __launch_bounds__(256) hyd_merge_bf16_kernel(const uint16_t* o_a
         const float inv = 1.f / tot;
         ca = wa * inv; cb = wb * inv;
     }
-    const u32x4 a = *reinterpret_cast<const u32x4*>(o_a + row * kHeadDim + c * 8);
-    const u32x4 b = *reinterpret_cast<const u32x4*>(o_b + row * kHeadDim + c * 8);
+    const u32x4 a = *reinterpret_cast<const u32x4*>(o_a + row * D + c * 8);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(o_b + row * D + c * 8);
     u32x4 r;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -40,7 +41,7 @@ __global__ void __launch_bounds__(256) hyd_merge_bf16_kernel(const uint16_t* o_a
         const float hi = (ca != 0.f ? ca * bf16_hi(a[e]) : 0.f) + (cb != 0.f ? cb * bf16_hi(b[e]) : 0.f);
         r[e] = pack_bf16(lo, hi);
     }
-    *reinterpret_cast<u32x4*>(o_out + row * kHeadDim + c * 8) = r;
+    *reinterpret_cast<u32x4*>(o_out + row * D + c * 8) = r;
     if (c == 0) lse_out[si] = lse;
 }
 

@@ -14,10 +14,11 @@ namespace hyd {
 constexpr int kRopeTok = 16;          // packed rows per workgroup
 constexpr int kRopeThreads = 256;
 
+template <int D = kHeadDim>
 __global__ void __launch_bounds__(kRopeThreads) hyd_rope_bf16_kernel(const uint16_t* x, const int32_t* __restrict__ cu,
                                                                      int nseq, int T, int heads, double log2_base,
                                                                      int inverse, uint16_t* out) {
-    constexpr int kHalf = kHeadDim / 2;
+    constexpr int kHalf = D / 2;
     __shared__ int pos[kRopeTok];
     __shared__ float cs[kRopeTok][kHalf][2];
     const int tid = threadIdx.x;
@@ -38,21 +39,23 @@ __global__ void __launch_bounds__(kRopeThreads) hyd_rope_bf16_kernel(const uint1
     __syncthreads();
     for (int e = tid; e < kRopeTok * kHalf; e += kRopeThreads) {
         const int r = e / kHalf, i = e % kHalf;
-        const double ang = (double)pos[r] * exp2(-(double)(2 * i) / kHeadDim * log2_base);
+        const double ang = (double)pos[r] * exp2(-(double)(2 * i) / D * log2_base);
         double s, c;
         sincos(inverse ? -ang : ang, &s, &c);
         cs[r][i][0] = (float)c;
         cs[r][i][1] = (float)s;
     }
     __syncthreads();
-    // eight lanes per (row, head): lane c owns elements [8c, 8c+8) and their partners [64+8c, 64+8c+8)
+    // eight lanes per (row, head), D/16 of them at work: lane c owns elements [8c, 8c+8) and their
+    // partners [D/2 + 8c, D/2 + 8c + 8)
     const int c8 = tid & 7, slot = tid >> 3;
     const int items = kRopeTok * heads;
     for (int it = slot; it < items; it += kRopeThreads / 8) {
         const int r = it / heads, h = it % heads;
         const int t = t0 + r;
         if (t >= T) break;
-        const int64_t off = ((int64_t)t * heads + h) * kHeadDim + 8 * c8;
+        if (D != kHeadDim && c8 >= D / 16) continue;
+        const int64_t off = ((int64_t)t * heads + h) * D + 8 * c8;
         const u32x4 lo = *reinterpret_cast<const u32x4*>(x + off);
         const u32x4 hi = *reinterpret_cast<const u32x4*>(x + off + kHalf);
         u32x4 olo, ohi;

@@ -68,7 +68,8 @@ def test_forward_argument_errors(lib):
     assert call_fwd(lib, hq=0) == HEADS
     assert call_fwd(lib, hq=4, hkv=3) == HEADS
     assert call_fwd(lib, d=96) == HEADDIM
-    assert call_fwd(lib, d=64) == HEADDIM                       # bf16 path is head_dim 128 only
+    assert call_fwd(lib, d=64, q=None) == NULL                  # head_dim 64 is valid for bf16 too
+    assert call_fwd(lib, d=64, T=1 << 19, max_len=1 << 19, hq=32, hkv=32) == SHAPE   # 2^19 * 32 * 64 * 2 = 2^31 bytes: the d = 64 limit
     assert call_fwd(lib, cu=None) == NULL
     assert call_fwd(lib, max_len=0) == SHAPE
     assert call_fwd(lib, max_len=257) == SHAPE
@@ -147,7 +148,7 @@ def test_merge_argument_errors(lib):
     assert lib.hyd_attn_merge(P, P, P, P, 100, 4, 128, 1, P, P, None) == 3      # bf16 only
     assert lib.hyd_attn_merge(P, P, P, P, -1, 4, 128, 0, P, P, None) == 2
     assert lib.hyd_attn_merge(P, P, P, P, 100, 0, 128, 0, P, P, None) == 4
-    assert lib.hyd_attn_merge(P, P, P, P, 100, 4, 64, 0, P, P, None) == 5
+    assert lib.hyd_attn_merge(P, P, P, P, 100, 4, 96, 0, P, P, None) == 5
     assert lib.hyd_attn_merge(P, P, None, P, 100, 4, 128, 0, P, P, None) == 1
     assert lib.hyd_attn_merge(None, None, None, None, 0, 4, 128, 0, None, None, None) == 0
 
@@ -157,7 +158,7 @@ def test_rope_argument_errors(lib):
     f = ctypes.c_float
     call = lambda **kw: lib.hyd_rope_packed(*[{**dict(x=P, cu=P, nseq=2, T=100, h=4, d=128, base=f(10000.0), inv=0, dt=0, out=P, st=None), **kw}[k]
                                               for k in ("x", "cu", "nseq", "T", "h", "d", "base", "inv", "dt", "out", "st")])
-    assert call(dt=1) == 3 and call(d=64) == 5 and call(h=0) == 4
+    assert call(dt=1) == 3 and call(d=96) == 5 and call(h=0) == 4
     assert call(T=-1) == 2 and call(nseq=0) == 2 and call(base=f(1.0)) == 2
     assert call(x=None) == 1 and call(cu=None) == 1 and call(out=None) == 1
     assert call(T=0, nseq=0, x=None, cu=None, out=None) == 0

@@ -61,6 +61,34 @@ def test_bf16_small(lengths, hq, hkv):
     full_parity(lengths, hq, hkv, 128, "bf16", seed=31)
 
 
+@pytest.mark.parametrize("lengths,hq,hkv", [
+    ([1, 7, 64, 184], 2, 2),
+    ([128, 129, 127, 1, 0, 256, 33], 4, 2),
+    ([513, 64, 300], 8, 8),
+    ([90, 1000, 31], 6, 3),
+    ([2100], 4, 1),
+])
+def test_bf16_head_dim_64(lengths, hq, hkv):
+    """The bf16 kernels at head_dim 64: same tiles, half the contraction steps and output blocks."""
+    full_parity(lengths, hq, hkv, 64, "bf16", seed=37)
+
+
+def test_bf16_head_dim_64_no_cross_contamination():
+    # rows of 128 bytes sit next to each other in memory (head h+1 follows head h): the loads that
+    # cover only half of a 256-byte LDS row must not pick up the neighbour
+    lengths, hq, hkv, d = [300, 129, 200], 4, 2, 64
+    cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 38)
+    scale = 1.0 / np.sqrt(d)
+    a = gu.run_gpu(cu, q, k, v, do, "bf16", scale)
+    q2, k2, v2, do2 = q.copy(), k.copy(), v.copy(), do.copy()
+    q2[:, 1] *= 3; k2[:, 1] *= -2; v2[:, 1] += 1; do2[:, 1] *= 0.5          # heads 1 (query) and 1 (KV) change
+    b = gu.run_gpu(cu, q2, k2, v2, do2, "bf16", scale)
+    # query heads 0, 1 use KV head 0; heads 2, 3 use KV head 1: head 0 and KV head 0's share from head 0 stay
+    assert np.array_equal(a["o"][:, 0], b["o"][:, 0]) and np.array_equal(a["lse"][0], b["lse"][0])
+    assert np.array_equal(a["dq"][:, 0], b["dq"][:, 0])
+    assert not np.array_equal(a["o"][:, 2], b["o"][:, 2])
+
+
 def test_bf16_thousands_of_short_sequences():
     # more sequences than the schedule prelude has threads, every item a single partial tile,
     # empty sequences in between

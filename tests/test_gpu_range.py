@@ -124,6 +124,31 @@ def test_ring_of_visits_merges_to_the_plain_forward(lengths, hq, hkv, cp):
     gu.check("lse", gu.to_np(acc_l), lse_ref, "bf16")
 
 
+def test_ring_at_head_dim_64():
+    lengths, hq, hkv, cp = [1300, 257, 600], 4, 2, 2
+    d = 64
+    cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 55)
+    scale = 1.0 / np.sqrt(d)
+    dev = [gu.to_dev(x, "bf16") for x in (q, k, v)]
+    cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
+    T = int(cu[-1])
+    bounds = [chunk_bounds(L, cp) for L in lengths]
+    acc_o = torch.zeros((T, hq, d), dtype=torch.bfloat16, device="cuda")
+    acc_l = torch.full((hq, T), float("-inf"), dtype=torch.float32, device="cuda")
+    part_o, part_l = torch.zeros_like(acc_o), torch.full_like(acc_l, float("-inf"))
+    for r in range(cp):
+        for c in range(r + 1):
+            ranges = [(b[r][0], b[r][1], b[c][0], b[c][1]) for b in bounds]
+            binding.varlen_attn_fwd_range(dev[0], dev[1], dev[2], cu_d, ranges, max(lengths), scale, part_o, part_l,
+                                          cu_seqlens_host=[int(x) for x in cu])
+            binding.attn_merge(acc_o, acc_l, part_o, part_l, out=acc_o, lse_out=acc_l)
+            part_o.zero_(); part_l.fill_(float("-inf"))
+    torch.cuda.synchronize()
+    o_ref, lse_ref = orc.fwd(q, k, v, cu, scale)
+    gu.check("o", gu.to_np(acc_o), o_ref, "bf16")
+    gu.check("lse", gu.to_np(acc_l), lse_ref, "bf16")
+
+
 def test_merge_kernel_alone():
     rng = np.random.default_rng(7)
     T, hq = 1000, 3

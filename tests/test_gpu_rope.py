@@ -38,6 +38,15 @@ def test_rope_forward_inverse_in_place(lengths, heads):
     assert torch.equal(y[starts], xd[starts])               # every sequence starts at position 0
 
 
+def test_rope_head_dim_64():
+    lengths, heads = [33, 1, 300], 3
+    cu = wl.cu_seqlens(lengths)
+    T = int(cu[-1])
+    x = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.random.default_rng(4).standard_normal((T, heads, 64)).astype(np.float32)))
+    y = binding.rope_packed(gu.to_dev(x, "bf16"), torch.from_numpy(cu).cuda())
+    check_rounded(gu.to_np(y), ro.rope_packed(x, cu))
+
+
 def test_rope_long_positions_and_rate():
     """One 65536-token sequence (angles up to 65535 rad: fp32 angles would fail here) next to
     short ones, 8 heads; sampled rows against the reference, and the achieved HBM rate."""
