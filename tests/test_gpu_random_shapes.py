@@ -30,8 +30,9 @@ def draw(seed):
 @pytest.mark.parametrize("seed", range(10))
 def test_random_shape(seed):
     lengths, hq, hkv, scale = draw(seed)
-    print(f"\nrandom shape seed={seed} lengths={lengths} hq={hq} hkv={hkv} scale={scale:.4f}", flush=True)
-    cu, q, k, v, do = wl.custom(lengths, hq, hkv, 128, "bf16", 70 + seed)
+    d = 64 if seed in (1, 4, 7) else 128
+    print(f"\nrandom shape seed={seed} lengths={lengths} hq={hq} hkv={hkv} d={d} scale={scale:.4f}", flush=True)
+    cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 70 + seed)
     # |dS| grows with the scale (sharper softmax, larger dP - D), and dS is rounded to bf16 before
     # its product: at scale 0.2 and unit-variance dO three of 100000 dQ entries of size 2-4 sat at
     # 2.7e-2, above the absolute bar by nothing but that rounding; the upstream gradient is scaled
@@ -49,7 +50,7 @@ def test_random_shape(seed):
         T = int(cu[-1])
         dev = [gu.to_dev(x, "bf16") for x in (q, k, v)]
         cu_d = torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda()
-        out = torch.full((T, hq, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+        out = torch.full((T, hq, d), 3.0, dtype=torch.bfloat16, device="cuda")
         ls = torch.full((hq, T), 9.0, dtype=torch.float32, device="cuda")
         binding.varlen_attn_fwd_range(dev[0], dev[1], dev[2], cu_d, ranges, max(lengths), scale, out, ls,
                                       cu_seqlens_host=[int(x) for x in cu])
