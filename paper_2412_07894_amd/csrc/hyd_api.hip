@@ -6,6 +6,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "hyd_bwd_bf16.h"
@@ -143,6 +144,7 @@ struct DeviceInfo {
     int occ_fwd = 1, occ_dq = 1, occ_kv = 1;
 };
 DeviceInfo g_dev[64];
+std::mutex g_dev_mutex;       // first use of a device from several host threads at once
 
 template <typename K>
 bool prep_kernel(K kernel, int threads, int lds, int* occ) {
@@ -159,6 +161,7 @@ hyd_status device_info(DeviceInfo** out) {
     if (hipGetDevice(&dev) != hipSuccess) return HYD_ERR_LAUNCH;
     if (dev < 0 || dev >= 64) return HYD_ERR_LAUNCH;
     DeviceInfo& d = g_dev[dev];
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
     if (!d.ready) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return HYD_ERR_LAUNCH;

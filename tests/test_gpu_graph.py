@@ -47,3 +47,41 @@ def test_step_in_a_hip_graph_replays_bit_exact():
         for name, got, want in zip(("o", "lse", "dq", "dk", "dv"), (o, lse, dq, dk, dv), ref):
             assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
                                want.view(torch.int16 if want.dtype == torch.bfloat16 else torch.int32)), (rep, name)
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere():
+    """Calls are re-entrant given distinct workspaces and outputs: two forward+backward steps of
+    different batches enqueued on two streams at once give the bits of running them one by one."""
+    import threading
+    import torch
+    from paper_2412_07894_amd import binding, workloads as wl
+    import gpu_util as gu
+    scale = 1.0 / np.sqrt(128)
+    batches = []
+    for seed, lengths in ((81, [900, 300, 2000]), (82, [64, 1500, 700, 33])):
+        cu, q, k, v, do = wl.custom(lengths, 8, 4, 128, "bf16", seed)
+        dev = [gu.to_dev(x, "bf16") for x in (q, k, v, do)]
+        batches.append((torch.from_numpy(np.asarray(cu, dtype=np.int32)).cuda(), dev, max(lengths)))
+
+    def run(b, stream, out):
+        cu_d, (qd, kd, vd, dod), ml = b
+        with torch.cuda.stream(stream):
+            o, lse = binding.varlen_attn_fwd(qd, kd, vd, cu_d, ml, scale, stream=stream)
+            out.extend([o, lse, *binding.varlen_attn_bwd(qd, kd, vd, o, lse, dod, cu_d, ml, scale, stream=stream)])
+
+    ref = [[], []]
+    for i, b in enumerate(batches):
+        run(b, torch.cuda.current_stream(), ref[i])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        got = [[], []]
+        threads = [threading.Thread(target=run, args=(batches[i], streams[i], got[i])) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        torch.cuda.synchronize()
+        for i in range(2):
+            for a, b in zip(got[i], ref[i]):
+                assert torch.equal(a, b)
