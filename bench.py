@@ -45,21 +45,24 @@ def gpu_inputs(cfg, lengths, seed, inputs="randn"):
 
 
 def mfma_probe():
-    """Sustained TFLOP/s of a pure bf16 MFMA loop (about 15 ms per pattern), zeros and random operands."""
+    """Sustained TFLOP/s of a pure bf16 MFMA loop and of the forward tile's instruction mix (about 15 ms per
+    launch), zeros and random operands."""
     import torch
     from paper_2412_07894_amd import binding
     res = {}
     binding.enable_kernel_timing(True)
-    for name, pattern in (("zeros", 0), ("random", 1)):
+    for name, pattern, iters in (("zeros", 0, 100000), ("random", 1, 100000), ("fwd_mix_zeros", 2, 20000), ("fwd_mix_random", 3, 20000)):
         best = 0.0
         for _ in range(3):
-            flops, _out = binding.probe_mfma(256, 100000, pattern)
+            flops, _out = binding.probe_mfma(256, iters, pattern)
             (kname, ms), = binding.kernel_times()
             best = max(best, flops / (ms * 1e-3) / 1e12)
         res[name] = best
     binding.enable_kernel_timing(False)
     res["unit"] = "TFLOP/s"
-    res["what"] = "256 workgroups x 8 waves of v_mfma_f32_32x32x16_bf16 on register operands, best of 3 launches"
+    res["what"] = ("256 workgroups x 8 waves of v_mfma_f32_32x32x16_bf16 on register operands, best of 3 launches; "
+                   "fwd_mix_*: the same MFMAs inside the forward tile's instruction mix (one LDS fragment per MFMA, the "
+                   "softmax arithmetic of one score per MFMA), no synchronisation")
     return res
 
 

@@ -569,17 +569,21 @@ void hyd_set_wg_trace(void* device_records, int capacity_records) {
 
 hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops, void* hip_stream) {
     if (!device_out || !flops) return HYD_ERR_NULL;
-    if (workgroups <= 0 || iters <= 0 || (pattern != 0 && pattern != 1)) return HYD_ERR_SHAPE;
+    if (workgroups <= 0 || iters <= 0 || pattern < 0 || pattern > 3) return HYD_ERR_SHAPE;
     DeviceInfo* dev = nullptr;
     const hyd_status st_dev = device_info(&dev);
     if (st_dev != HYD_OK) return st_dev;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     {
         KernelTimer kt("probe_mfma", st);
-        hipLaunchKernelGGL(hyd_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern);
+        if (pattern < 2)
+            hipLaunchKernelGGL(hyd_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern);
+        else
+            hipLaunchKernelGGL(hyd_probe_mix_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern - 2);
     }
     if (hipGetLastError() != hipSuccess) return HYD_ERR_LAUNCH;
-    *flops = (double)workgroups * (kProbeThreads / 64) * (double)iters * kProbeMfmaPerIter * (2.0 * 32 * 32 * 16);
+    *flops = (double)workgroups * (kProbeThreads / 64) * (double)iters * (pattern < 2 ? kProbeMfmaPerIter : kProbeMixMfmaPerIter) *
+             (2.0 * 32 * 32 * 16);
     return HYD_OK;
 }
 

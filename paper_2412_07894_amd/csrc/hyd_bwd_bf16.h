@@ -13,8 +13,10 @@
 namespace hyd {
 
 // ---------------------------------------------------------------------------------------------
-// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32) and LSE2 = LSE * log2(e), the form in which the
-// two backward kernels consume them (P = exp2(s * scale * log2(e) - LSE2)).  16 lanes per row.
+// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32) and LSE2 = LSE * log2(e), both stored NEGATED:
+// the form in which the two backward kernels consume them (P = exp2(s * scale * log2(e) + (-LSE2)),
+// dS = P * (dP + (-D))), so that dK/dV can use them as initial values of its score and dP
+// accumulators.  16 lanes per row.
 // ---------------------------------------------------------------------------------------------
 constexpr float kLog2e = 1.44269504088896340736f;
 
@@ -40,14 +42,14 @@ __global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t
     acc += __shfl_xor(acc, 8, 64);
     if (row < n_rows && c == 0) {
         const int t = (int)(row / hq), h = (int)(row % hq);
-        D[(int64_t)h * T + t] = acc;
-        lse2[(int64_t)h * T + t] = lse[(int64_t)h * T + t] * kLog2e;
+        D[(int64_t)h * T + t] = -acc;
+        lse2[(int64_t)h * T + t] = -lse[(int64_t)h * T + t] * kLog2e;
     }
 }
 
 struct BwdParams {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
-    const float* lse2; const float* D;      // LSE * log2(e) and rowsum(dO * O), both [Hq][T]
+    const float* lse2; const float* D;      // -LSE * log2(e) and -rowsum(dO * O), both [Hq][T]
     uint16_t* dq; uint16_t* dk; uint16_t* dv;
     int T, hq, hkv;
     float scale, scale_log2;
@@ -86,6 +88,7 @@ template <int D>
 __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int kb,
                                          const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], f32x16 (&acc)[D / 32],
                                          float scale_log2, float lse2, float Dq, bool mask, int krel) {
+    // lse2 and Dq hold -LSE2 and -D of the lane's row
     constexpr int NK = D / 16, NDB = D / 32;
     // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
@@ -119,9 +122,9 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     }
     auto ds_pair = [&](int j) -> uint32_t {   // scores 2j, 2j+1 of the 16 a lane holds
         const int r = 2 * j;
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lse2));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], scale_log2, -lse2));
-        return pack_bf16(p0 * (dp[r] - Dq), p1 * (dp[r + 1] - Dq));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, lse2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], scale_log2, lse2));
+        return pack_bf16(p0 * (dp[r] + Dq), p1 * (dp[r + 1] + Dq));
     };
     u32x4 dcur, dnxt;
 #pragma unroll
@@ -304,7 +307,11 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
 // accumulators (two waves fit one SIMD) and each hides the other's non-MFMA work:
 //     role A (waves 0-3): S = Q K^T  -> P = exp2(S*scale - LSE2) -> hands P to its partner through
 //                         LDS -> dV^T += dO^T P
-//     role B (waves 4-7): dP = dO V^T -> takes P -> dS = P (dP - D) -> dK^T += Q^T dS
+//     role B (waves 4-7): dP' = dO V^T - D -> takes P -> dS = P dP' -> dK^T += Q^T dS
+// -D of the block's rows is the INITIAL VALUE of role B's dP accumulator, read from the stage into
+// the accumulator registers: the MFMA chain then delivers the factor of dS itself and the
+// subtraction per element leaves the vector ALU (role A cannot do the same with -LSE2 without a
+// pre-scaled K, whose rounding to bf16 costs a quarter more error in dK and dV).
 // S[i][j] and dP[i][j] put one KEY in each lane (accumulator column) and query rows in the slots,
 // so P and dS are directly the B fragments (contraction index = query row) of the second
 // products, whose A fragments come from the transposing LDS read of the dO and Q tiles.  P crosses
@@ -454,12 +461,15 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         }
         __builtin_amdgcn_s_barrier();                         // stage 2 and the P area may be written now
 
-        // one 32-row block: rows 32*ib.. of the tile in `base`; `parity` selects the P buffer
-        auto block = [&](int base, int ib, int parity, int qt0) {         // base: LDS offset of the stage
+        // one 32-row block: rows 32*ib.. of the tile in `base`; `parity` selects the P buffer.  The role
+        // is a compile-time tag: each role runs its own copy of the tile loop, so that no register
+        // has to be reconciled where the roles' paths would join.
+        auto block = [&](auto role_tag, int base, int ib, int parity, int qt0) {       // base: LDS offset of the stage
+            constexpr bool kB = decltype(role_tag)::value;
             // the role's choice of tile (first product reads Q (A) / dO (B), second product reads
             // dO (A) / Q (B)) is folded into fa.row / fa.col once per kernel
             const int T1 = base, T2 = base;
-            const float* stat = reinterpret_cast<const float*>(smem + base + 2 * kKvTileBytes) + (role_b ? kKvBM : 0);
+            const float* stat = reinterpret_cast<const float*>(smem + base + 2 * kKvTileBytes) + (kB ? kKvBM : 0);
             const int ifirst = qt0 + 32 * ib;                 // first query row of the block
             const bool work = active && ifirst + 31 >= wkey0; // some row sees some key of the pair
             f32x16 x;
@@ -468,8 +478,15 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             LdsQueue lq{0};
             ColFrag cf[kCAhead];
             if (work) {
+                // accumulator slot 4*rq + e holds row 8*rq + 4*half + e of the block: role B's product
+                // starts from -D of that row, role A's from zero (its statistic enters after the scale)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) x[r] = 0.f;
+                for (int rq = 0; rq < 4; ++rq) {
+                    f32x4 i4 = {0.f, 0.f, 0.f, 0.f};
+                    if (kB) i4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[4 * rq + e] = i4[e];
+                }
                 constexpr int kAhead = NK < 6 ? NK : 6;
                 bf16x8 f[kAhead];
 #pragma unroll
@@ -481,7 +498,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                     if (i + kAhead < NK) f[i % kAhead] = frag_row(T1, fa, ib, i + kAhead);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (!role_b) {
+                if (!kB) {
                     if (ifirst < wkey0 + 31) {                // the block straddles the diagonal
                         const int irel = key - ifirst;
 #pragma unroll
@@ -490,11 +507,11 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                     }
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
-                        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
+                        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);   // -LSE2
                         f32x4 pv;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, -l4[e]));
+                            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, l4[e]));
                         *reinterpret_cast<f32x4*>(pbuf + parity * kKvPBytes + rq * 1024) = pv;
                         pk[2 * rq] = pack_bf16(pv[0], pv[1]);
                         pk[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
@@ -514,13 +531,12 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             }
             __builtin_amdgcn_s_barrier();
             if (work) {
-                if (role_b) {
+                if (kB) {
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
-                        const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
                         const f32x4 pv = *reinterpret_cast<const f32x4*>(pbuf + parity * kKvPBytes + rq * 1024);
-                        pk[2 * rq] = pack_bf16(pv[0] * (x[4 * rq] - d4[0]), pv[1] * (x[4 * rq + 1] - d4[1]));
-                        pk[2 * rq + 1] = pack_bf16(pv[2] * (x[4 * rq + 2] - d4[2]), pv[3] * (x[4 * rq + 3] - d4[3]));
+                        pk[2 * rq] = pack_bf16(pv[0] * x[4 * rq], pv[1] * x[4 * rq + 1]);
+                        pk[2 * rq + 1] = pack_bf16(pv[2] * x[4 * rq + 2], pv[3] * x[4 * rq + 3]);
                     }
                 }
                 // the bookkeeping of the reads issued before the barrier, restated as constants
@@ -538,13 +554,13 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 }
             }
         };
-        auto step = [&](auto stage_tag, int it) {
+        auto step = [&](auto role_tag, auto stage_tag, int it) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int ST2 = (ST + 2) % kKvStages;
             constexpr int base = ST * kKvStageBytes;
             const bool more2 = it + 2 < n_iter;
             const int qt0 = (qt_first + it / G) * kKvBM;
-            block(base, 0, 0, qt0);
+            block(role_tag, base, 0, 0, qt0);
             // every wave has passed this step's first barrier, hence finished the previous step:
             // the stage that held it may be overwritten now
             if (more2) dma_stage(it + 2, ST2);
@@ -552,13 +568,17 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             // step ago and precede this step's loads in the (in-order) vmcnt queue
             if (more2) __builtin_amdgcn_s_waitcnt(0x0F70 | (kDmaPerStage & 15) | ((kDmaPerStage >> 4) << 14));
             else __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-            block(base, 1, 1, qt0);
+            block(role_tag, base, 1, 1, qt0);
         };
-        for (int it = 0; it < n_iter; it += 3) {
-            step(std::integral_constant<int, 0>{}, it);
-            if (it + 1 < n_iter) step(std::integral_constant<int, 1>{}, it + 1);
-            if (it + 2 < n_iter) step(std::integral_constant<int, 2>{}, it + 2);
-        }
+        auto tiles = [&](auto role_tag) {
+            for (int it = 0; it < n_iter; it += 3) {
+                step(role_tag, std::integral_constant<int, 0>{}, it);
+                if (it + 1 < n_iter) step(role_tag, std::integral_constant<int, 1>{}, it + 1);
+                if (it + 2 < n_iter) step(role_tag, std::integral_constant<int, 2>{}, it + 2);
+            }
+        };
+        if (role_b) tiles(std::true_type{});
+        else tiles(std::false_type{});
         __syncthreads();                                      // every wave is done with the ring
         if (active)
             store_rows_via_lds<D>((role_b ? p.dk : p.dv) + (int64_t)(row0 + wkey0) * kv_stride + (int64_t)g * D, kv_stride,
