@@ -229,9 +229,14 @@ __device__ __forceinline__ void dma_rows(const __amdgpu_buffer_rsrc_t& rs, char*
     }
 }
 
-__device__ __forceinline__ float shfl_xor32(float v) {
-    // exchange with the lane 32 away (the other half of the wave)
-    return __shfl_xor(v, 32, 64);
+// Both halves' values of v in every lane: lo = v of lane l % 32, hi = v of lane l % 32 + 32.  One
+// v_permlane32_swap (gfx950) instead of a trip through LDS, whose wait would also drain every
+// fragment read in flight.
+__device__ __forceinline__ void both_halves(float v, float& lo, float& hi) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // swaps r[0]'s upper half with r[1]'s lower half
+    lo = __uint_as_float(r[0]);
+    hi = __uint_as_float(r[1]);
 }
 
 }  // namespace hyd

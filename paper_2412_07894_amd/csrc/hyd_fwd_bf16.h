@@ -116,7 +116,11 @@ __device__ __forceinline__ void fwd_tile(int Kt, int Vt, const FragAddr& fa, con
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = fmaxf(mx, shfl_xor32(mx));
+    {
+        float lo, hi;
+        both_halves(mx, lo, hi);
+        mx = fmaxf(lo, hi);
+    }
     const float cand = mx * scale_log2;
     if (__builtin_expect(__any(cand > m_ref + kRefSlack), 0)) {   // a row left the slack window
         const float m_new = fmaxf(m_ref, cand);
@@ -303,7 +307,9 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
             if (t + 2 < n_kt) step(std::integral_constant<int, 2>{}, t + 2);
         }
         // epilogue: normalise, write O (bf16) and LSE (natural log)
-        const float l_tot = l_run + shfl_xor32(l_run);
+        float l_lo, l_hi;
+        both_halves(l_run, l_lo, l_hi);
+        const float l_tot = l_lo + l_hi;
         // range variant: a row below the key range has l = 0, m = -inf: O = 0, LSE = -inf
         const float inv = (R && !(l_tot > 0.f)) ? 0.f : 1.f / l_tot;
         if (active) {
