@@ -94,18 +94,31 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+
     {
         // fragment i < NK: K, contraction step i; i >= NK: V, step i - NK; reads run kAhead ahead
-        constexpr int kAhead = 6;
+        constexpr int kAhead = 4;
         bf16x8 f[kAhead];
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) f[i] = frag_row(i < NK ? Kt : Vt, fa, kb, i % NK);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2 * NK; ++i) {
+            if (i == NK && mask) {                // the score block is complete; hidden keys: P = exp2(-inf) = 0
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (8 * (r >> 2) + (r & 3) + krel > 0) s[r] = -INFINITY;
+            }
             if (i < NK) s = mfma32(f[i % kAhead], qf[i], s);
             else dp = mfma32(f[i % kAhead], dof[i - NK], dp);
             if (i + kAhead < 2 * NK) f[i % kAhead] = frag_row(i + kAhead < NK ? Kt : Vt, fa, kb, (i + kAhead) % NK);
+            if (i >= NK) {                        // the exponentials of the finished score block run under the dP product
+#pragma unroll
+                for (int e = 0; e < 16 / NK; ++e) {
+                    const int r = (16 / NK) * (i - NK) + e;
+                    s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, lse2));    // s becomes P in place
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -115,16 +128,9 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
 #pragma unroll
     for (int i = 0; i < kCAhead && i < 2 * NDB; ++i) issue_col(lq, cf[i], Kt, fa, 2 * kb + i / NDB, i % NDB);
     __builtin_amdgcn_sched_barrier(0);
-    if (mask) {                               // hidden keys: P = exp2(-inf) = 0
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (8 * (r >> 2) + (r & 3) + krel > 0) s[r] = -INFINITY;
-    }
     auto ds_pair = [&](int j) -> uint32_t {   // scores 2j, 2j+1 of the 16 a lane holds
         const int r = 2 * j;
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, lse2));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], scale_log2, lse2));
-        return pack_bf16(p0 * (dp[r] + Dq), p1 * (dp[r + 1] + Dq));
+        return pack_bf16(s[r] * (dp[r] + Dq), s[r + 1] * (dp[r + 1] + Dq));     // s holds P by now
     };
     u32x4 dcur, dnxt;
 #pragma unroll
@@ -487,6 +493,13 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[4 * rq + e] = i4[e];
                 }
+                // role A's -LSE2 values are requested before the product, so that they are there when
+                // the scores are (LDS reads return in order: the first fragment's wait covers them)
+                f32x4 l4[4];
+                if (!kB) {
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) l4[rq] = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);
+                }
                 constexpr int kAhead = NK < 6 ? NK : 6;
                 bf16x8 f[kAhead];
 #pragma unroll
@@ -507,11 +520,11 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                     }
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
-                        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 32 * ib + 8 * rq + 4 * half);   // -LSE2
+                        const f32x4 l4r = l4[rq];                                     // -LSE2
                         f32x4 pv;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, l4[e]));
+                            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, l4r[e]));
                         *reinterpret_cast<f32x4*>(pbuf + parity * kKvPBytes + rq * 1024) = pv;
                         pk[2 * rq] = pack_bf16(pv[0], pv[1]);
                         pk[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
