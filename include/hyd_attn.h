@@ -69,7 +69,8 @@ const char* hyd_status_string(hyd_status st);
  * (is_bwd = 1) needs for these sizes.  The workspace holds the work-item schedule (the list of
  * (sequence, tile) items ordered by decreasing cost, and the queue cursors of the persistent
  * workgroups) and, for the backward, two float vectors [Hq][T]: D = rowsum(dO * O) and LSE in
- * base-2 units.  Returns 0 for invalid arguments.  Pure host arithmetic: no HIP call.
+ * base-2 units (the bf16 kernels keep both negated; their contents are private to the library).
+ * Returns 0 for invalid arguments.  Pure host arithmetic: no HIP call.
  */
 size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, int hkv,
                                        int head_dim, hyd_dtype dt, int is_bwd);
