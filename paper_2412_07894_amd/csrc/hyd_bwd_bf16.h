@@ -410,9 +410,13 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         // its query tiles at the same pace and find some of each other's Q / dO tiles in L2;
         // every wave issues exactly kDmaPerStage loads, so that a vmcnt wait can tell stages apart
         constexpr int kDmaPerStage = 2 * (16 / kKvWaves) + 1;
-        auto dma_stage = [&](int it, int stage) {
-            const int h = g * G + it % G;
-            const int qt = qt_first + it / G;
+        // the loads are issued for it = 0, 1, 2, ... in turn: (tile, head) advance with them instead
+        // of being divided out of `it` every time
+        int ld_qt = qt_first, ld_h = 0;
+        auto dma_stage = [&](int stage) {
+            const int h = g * G + ld_h;
+            const int qt = ld_qt;
+            if (++ld_h == G) { ld_h = 0; ++ld_qt; }
             const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * D;
             const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + base, q_bytes);
             const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.d_o + base, q_bytes);
@@ -433,8 +437,8 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + which * kKvBM * 4),
                                                      4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
         };
-        if (n_iter > 0) dma_stage(0, 0);
-        if (n_iter > 1) dma_stage(1, 1);
+        if (n_iter > 0) dma_stage(0);
+        if (n_iter > 1) dma_stage(1);
 
         {   // keys j0 .. j0+127 of K and V of this KV head; rows past the key range read as zeros
             static_assert(kKvBN == 128 && kKvPairs * 2 * kKvPBytes >= kKvBN * kRowBytes, "K/V staging");
@@ -567,16 +571,18 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 }
             }
         };
+        int cp_qt = qt_first, cp_h = 0;
         auto step = [&](auto role_tag, auto stage_tag, int it) {
             constexpr int ST = decltype(stage_tag)::value;
             constexpr int ST2 = (ST + 2) % kKvStages;
             constexpr int base = ST * kKvStageBytes;
             const bool more2 = it + 2 < n_iter;
-            const int qt0 = (qt_first + it / G) * kKvBM;
+            const int qt0 = cp_qt * kKvBM;                    // the steps advance through (tile, head) like the loads
+            if (++cp_h == G) { cp_h = 0; ++cp_qt; }
             block(role_tag, base, 0, 0, qt0);
             // every wave has passed this step's first barrier, hence finished the previous step:
             // the stage that held it may be overwritten now
-            if (more2) dma_stage(it + 2, ST2);
+            if (more2) dma_stage(ST2);
             // the barrier of the second block also opens the next stage: its loads were issued one
             // step ago and precede this step's loads in the (in-order) vmcnt queue
             if (more2) __builtin_amdgcn_s_waitcnt(0x0F70 | (kDmaPerStage & 15) | ((kDmaPerStage >> 4) << 14));
