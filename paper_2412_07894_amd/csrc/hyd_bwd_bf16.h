@@ -547,6 +547,12 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 __builtin_amdgcn_s_waitcnt(0xc07f);
             }
             __builtin_amdgcn_s_barrier();
+            // Role B is served first on the SIMD the pair shares from here to the end of its dK product:
+            // it comes out of the barrier with the longer way to go (the P values have to come back
+            // from LDS before it can form dS, while role A's dV operands are in registers), and
+            // without the priority its dK MFMAs alternate with A's next score chain, which makes B
+            // the late one at the next barrier (A waited 16 % of a block for it, now both wait 5-7 %).
+            if (kB) __builtin_amdgcn_s_setprio(3);
             if (work) {
                 if (kB) {
 #pragma unroll
@@ -570,6 +576,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            if (kB) __builtin_amdgcn_s_setprio(0);
         };
         int cp_qt = qt_first, cp_h = 0;
         auto step = [&](auto role_tag, auto stage_tag, int it) {
