@@ -563,9 +563,10 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
                         const f16x4 hv = *reinterpret_cast<const f16x4*>(pbuf + parity * kKvPBytes + rq * 512);
-                        const f32x4 pv = {(float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]};
-                        pk[2 * rq] = pack_bf16(pv[0] * x[4 * rq], pv[1] * x[4 * rq + 1]);
-                        pk[2 * rq + 1] = pack_bf16(pv[2] * x[4 * rq + 2], pv[3] * x[4 * rq + 3]);
+                        // written as fused multiply-adds with a zero addend so that the fp16 factor is
+                        // converted inside the instruction (v_fma_mix_f32) instead of by one of its own
+                        pk[2 * rq] = pack_bf16(__builtin_fmaf((float)hv[0], x[4 * rq], 0.f), __builtin_fmaf((float)hv[1], x[4 * rq + 1], 0.f));
+                        pk[2 * rq + 1] = pack_bf16(__builtin_fmaf((float)hv[2], x[4 * rq + 2], 0.f), __builtin_fmaf((float)hv[3], x[4 * rq + 3], 0.f));
                     }
                 }
                 // the bookkeeping of the reads issued before the barrier, restated as constants
