@@ -3,12 +3,13 @@ error metrics of the acceptance bar (per output tensor, in float64):
     max-abs = max |gpu - ref|,   rel-L2 = ||gpu - ref||_2 / ||ref||_2
 bf16: max-abs <= 2e-2 and rel-L2 <= 5e-3;  fp32: both <= 1e-5.
 
-The bf16 max-abs bar needs one derived exception.  Outputs are stored as bf16, and rounding to
-nearest alone errs by up to half an ulp: 2^-7 for |x| in [4,8), 2^-6 in [8,16), 2^-5 in [16,32).
-From |x| >= 8 on that exceeds 2e-2 by itself, and in [4,8) it leaves the arithmetic only 4e-3.
-So an element passes if |err| <= max(2e-2, half_ulp_bf16(ref) + 1e-2): the stated 2e-2 wherever
-the format allows it (|ref| < 4), and "format rounding plus 1e-2 of arithmetic error" above.
-Every report line also shows max|ref| and how many elements needed the exception."""
+The bf16 max-abs bar has one exception, and only where the storage format forces it.  Outputs are
+stored as bf16 (8 significant bits); rounding to nearest alone errs by up to half a step:
+2^-7 = 0.0078 for |x| in [2,4), 2^-6 = 0.0156 in [4,8), 2^-5 = 0.0313 in [8,16), 2^-4 in [16,32).
+From |x| >= 8 on that exceeds 2e-2 by itself, so there (and only there) an element passes if
+|err| <= half_step_bf16(ref) + BIG_EPS: the rounding of the result plus a stated allowance for the
+arithmetic before it.  Below 8 the stated 2e-2 stands.  Every report line shows max|ref| and, per
+band of |ref|, how many elements there are, how many exceed 2e-2 and the largest error."""
 import numpy as np
 import torch
 
@@ -56,22 +57,57 @@ def half_ulp_bf16(x):
     return 2.0 ** (np.floor(np.log2(a)) - 8)
 
 
-def check(name, got, ref, dtype, report=None):
+BIG_EPS = 5e-3          # arithmetic allowance on top of the format's half step where |ref| >= 8
+BANDS = ((0.0, 1.0), (1.0, 2.0), (2.0, 4.0), (4.0, 8.0), (8.0, np.inf))
+
+
+def band_report(err, ref, bar):
+    """Per band of |ref|: elements, elements whose error exceeds `bar`, largest error."""
+    a = np.abs(ref)
+    parts = []
+    for lo, hi in BANDS:
+        m = (a >= lo) & (a < hi)
+        n = int(np.count_nonzero(m))
+        if n:
+            e = err[m]
+            parts.append(f"[{lo:g},{hi:g}): n={n} over={int(np.count_nonzero(e > bar))} max={float(e.max()):.3e}")
+    return "; ".join(parts)
+
+
+def tolerance(ref, dtype):
+    ta, _ = TOL[dtype]
+    tol = np.full(ref.shape, ta)
+    if dtype == "bf16":
+        big = np.abs(ref) >= 8.0
+        tol[big] = half_ulp_bf16(ref[big]) + BIG_EPS
+    return tol
+
+
+def check(name, got, ref, dtype, report=None, failures=None):
+    """Asserts the bar.  With `failures` (a list) a miss is appended there instead of raised, so
+    that a test can print every tensor before it fails."""
     max_abs, rel = errors(got, ref)
     ta, tr = TOL[dtype]
     err = np.abs(got - ref)
-    tol = np.full(ref.shape, ta)
-    if dtype == "bf16":
-        tol = np.maximum(tol, half_ulp_bf16(ref) + 1e-2)
-    n_exc = int(np.count_nonzero(err > ta))
+    tol = tolerance(ref, dtype)
     line = (f"{name}: max-abs {max_abs:.3e} (tol {ta:.0e})  rel-L2 {rel:.3e} (tol {tr:.0e})  "
-            f"max|ref| {np.max(np.abs(ref)) if ref.size else 0:.3f}  elements over {ta:.0e} (format-limited): {n_exc}")
+            f"max|ref| {np.max(np.abs(ref)) if ref.size else 0:.3f}  n={ref.size}  bands {band_report(err, ref, ta)}")
     print(line, flush=True)
     if report is not None:
         report.append(line)
-    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
-    assert np.all(err <= tol), line
-    assert rel <= tr, line
+    bad = []
+    if not np.all(np.isfinite(got)):
+        bad.append(f"{name}: non-finite values")
+    n_bad = int(np.count_nonzero(err > tol))
+    if n_bad:
+        bad.append(f"{name}: {n_bad} elements beyond the max-abs bar | {line}")
+    if rel > tr:
+        bad.append(f"{name}: rel-L2 beyond the bar | {line}")
+    if failures is not None:
+        failures.extend(bad)
+    else:
+        assert not bad, "\n".join(bad)
+    return max_abs, rel
 
 
 def sample_rows(cu, hq, rng, n_random):

@@ -2,7 +2,9 @@
 times (one call over the concatenation of all buffers).  The fp64 oracle cannot run these sizes
 in full, so it computes sampled outputs one by one: rows of O, LSE and dQ (each needs only its
 own sequence prefix) and rows of dK and dV for sampled keys of chosen (sequence, KV head) pairs.
-Samples always include sequence starts and ends, tile boundaries and the longest sequence."""
+Samples always include sequence starts and ends, tile boundaries and the longest sequence, whose
+sampled keys reach down to key 0 (the keys with the longest sums).  Every check prints the number
+of elements it covers and their share of the tensor."""
 import time
 
 import numpy as np
@@ -16,7 +18,7 @@ import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-def run_config(cid, n_rows=160, col_cases=3):
+def run_config(cid, n_rows=2000, col_cases=3, n_random_keys=48):
     cfg = wl.CONFIGS[cid]
     lengths = wl.seqlens(cid)
     cu = wl.cu_seqlens(lengths)
@@ -42,9 +44,13 @@ def run_config(cid, n_rows=160, col_cases=3):
     ro, rlse, rdq = orc.rows(q, k, v, do, cu, cfg.scale, toks, heads)
     print(f"oracle: {len(toks)} sampled rows in {time.time() - t0:.1f}s", flush=True)
     ti, hi = torch.from_numpy(toks.astype(np.int64)).cuda(), torch.from_numpy(heads.astype(np.int64)).cuda()
-    gu.check("o[rows]", gu.to_np(o[ti, hi]), ro, "bf16")
-    gu.check("lse[rows]", gu.to_np(lse[hi, ti]), rlse, "bf16")
-    gu.check("dq[rows]", gu.to_np(dq[ti, hi]), rdq, "bf16")
+    failures = []
+    n_q, n_kv = T * cfg.hq * cfg.d, T * cfg.hkv * cfg.d
+    print(f"covered: {ro.size} of {n_q} elements of O and of dQ ({ro.size / n_q:.2e}), "
+          f"{rlse.size} of {T * cfg.hq} of LSE ({rlse.size / (T * cfg.hq):.2e})", flush=True)
+    gu.check("o[rows]", gu.to_np(o[ti, hi]), ro, "bf16", failures=failures)
+    gu.check("lse[rows]", gu.to_np(lse[hi, ti]), rlse, "bf16", failures=failures)
+    gu.check("dq[rows]", gu.to_np(dq[ti, hi]), rdq, "bf16", failures=failures)
     # dK / dV of sampled keys: the longest sequence, a mid-sized one and a short one
     lens = np.diff(cu)
     order = np.argsort(-lens)
@@ -53,17 +59,21 @@ def run_config(cid, n_rows=160, col_cases=3):
     for n, s in enumerate(picks):
         L = int(lens[s])
         g = int(rng.integers(0, cfg.hkv))
-        cols = sorted({0, 1, 31, 32, 127, 128, L // 3, L // 2, L - 129, L - 33, L - 2, L - 1} & set(range(L)))
-        if n == 0:                  # keep the big one affordable: its cost is that of every row >= min(cols)
-            cols = [c for c in cols if c >= L // 3] or cols
-        cols = np.array(cols, dtype=np.int32)
+        # key 0 is always in: the cost is that of every row of the sequence for the group's
+        # heads whatever the keys are, so more keys are nearly free
+        cols = {0, 1, 2, 31, 32, 63, 64, 127, 128, 255, 256, L // 3, L // 2, L - 129, L - 33, L - 2, L - 1}
+        cols |= {int(c) for c in rng.integers(0, L, n_random_keys)}
+        cols = np.array(sorted(cols & set(range(L))), dtype=np.int32)
         t0 = time.time()
         a, b = orc.cols(q, k, v, do, cu, cfg.scale, s, g, cols)
         print(f"oracle: dK/dV of {len(cols)} keys of sequence {s} (L={L}), KV head {g} in {time.time() - t0:.1f}s", flush=True)
         idx = torch.from_numpy((cu[s] + cols).astype(np.int64)).cuda()
         gk.append(gu.to_np(dk[idx, g])); gv.append(gu.to_np(dv[idx, g])); rk.append(a); rv.append(b)
-    gu.check("dk[keys]", np.concatenate(gk), np.concatenate(rk), "bf16")
-    gu.check("dv[keys]", np.concatenate(gv), np.concatenate(rv), "bf16")
+    rk, rv = np.concatenate(rk), np.concatenate(rv)
+    print(f"covered: {rk.size} of {n_kv} elements of dK and of dV ({rk.size / n_kv:.2e})", flush=True)
+    gu.check("dk[keys]", np.concatenate(gk), rk, "bf16", failures=failures)
+    gu.check("dv[keys]", np.concatenate(gv), rv, "bf16", failures=failures)
+    assert not failures, "\n".join(failures)
 
 
 @pytest.mark.parametrize("cid", [2, 3, 4, 5])

@@ -23,26 +23,24 @@ def draw(seed):
         lengths[0] = 5
     hkv = int(rng.choice([1, 2, 3, 8]))
     g = int(rng.choice([1, 2, 4]))
-    scale = float(rng.choice([1.0 / np.sqrt(128), 0.03, 0.2]))
-    return lengths, hkv * g, hkv, scale
+    rng.choice([0, 1, 2])           # (a draw that older versions of this file spent on the scale)
+    return lengths, hkv * g, hkv
 
 
 @pytest.mark.parametrize("seed", range(10))
 def test_random_shape(seed):
-    lengths, hq, hkv, scale = draw(seed)
+    lengths, hq, hkv = draw(seed)
     d = 64 if seed in (1, 4, 7) else 128
+    scale = 1.0 / float(np.sqrt(d))         # the benchmark configurations' scale, unit-variance dO
     print(f"\nrandom shape seed={seed} lengths={lengths} hq={hq} hkv={hkv} d={d} scale={scale:.4f}", flush=True)
     cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 70 + seed)
-    # |dS| grows with the scale (sharper softmax, larger dP - D), and dS is rounded to bf16 before
-    # its product: at scale 0.2 and unit-variance dO three of 100000 dQ entries of size 2-4 sat at
-    # 2.7e-2, above the absolute bar by nothing but that rounding; the upstream gradient is scaled
-    # down with the scale (a power of two, exact) so that the case tests shapes, not the bar
-    do = do * np.float32(0.125 if scale > 0.1 else 0.5)
     got = gu.run_gpu(cu, q, k, v, do, "bf16", scale, host_cu=bool(seed & 1))
     o, lse = orc.fwd(q, k, v, cu, scale)
     dq, dk, dv = orc.bwd(q, k, v, do, cu, scale)
+    failures = []
     for name, ref in (("o", o), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
-        gu.check(name, got[name], ref, "bf16")
+        gu.check(name, got[name], ref, "bf16", failures=failures)
+    assert not failures, "\n".join(failures)
     # one range visit: queries from row 256 on against the keys before them
     if max(lengths) > 256:
         A = binding.RANGE_ALIGN
