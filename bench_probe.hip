@@ -1,10 +1,14 @@
-// Sustained-rate probe of the bf16 matrix pipe: nothing but v_mfma_f32_32x32x16_bf16 on register
-// operands, two waves per SIMD, four independent accumulator chains per wave.  It answers the
-// question the attention kernels' roofline fraction depends on: what this board sustains when the
-// matrix pipe is never starved.  The answer depends on the operand DATA (power management lowers
-// the clock when operands toggle many bits), so the pattern is an argument.
-#pragma once
-#include "hyd_device.h"
+// Bench-only helper (not part of the product library): sustained-rate probes of the bf16 matrix
+// pipe, which bench.py prints beside the roofline to say what this board sustains when the matrix
+// pipe is never starved.  The answer depends on the operand DATA (power management lowers the
+// clock when operands toggle many bits), so the pattern is an argument.
+//   patterns 0 / 1: nothing but v_mfma_f32_32x32x16_bf16 on register operands (zeros / random),
+//                   two waves per SIMD, four independent accumulator chains per wave
+//   patterns 2 / 3: the same instruction inside the forward kernel's steady-state instruction mix
+// Built by __graft_entry__.build() into bench_probe.so; one C entry point, bench_probe_mfma.
+#include <hip/hip_runtime.h>
+
+#include "paper_2412_07894_amd/csrc/hyd_device.h"
 
 namespace hyd {
 
@@ -12,7 +16,7 @@ constexpr int kProbeThreads = 512;
 constexpr int kProbeMfmaPerIter = 4;
 
 // pattern 0: all operands zero; pattern 1: pseudo-random bf16 values of magnitude around one
-__global__ void __launch_bounds__(kProbeThreads) hyd_probe_mfma_kernel(float* out, int iters, int pattern) {
+__global__ void __launch_bounds__(kProbeThreads) bench_probe_mfma_kernel(float* out, int iters, int pattern) {
     uint32_t h = (blockIdx.x * kProbeThreads + threadIdx.x) * 2654435761u + 12345u;
     auto next_pair = [&]() -> uint32_t {            // two bf16 values in [1, 2) with random mantissas and signs
         h = h * 1664525u + 1013904223u;
@@ -54,7 +58,7 @@ __global__ void __launch_bounds__(kProbeThreads) hyd_probe_mfma_kernel(float* ou
 constexpr int kProbeMixMfmaPerIter = 16;
 constexpr int kProbeMixLds = 16384;                    // 16 fragments of 1 KB
 
-__global__ void __launch_bounds__(kProbeThreads, 1) hyd_probe_mix_kernel(float* out, int iters, int pattern) {
+__global__ void __launch_bounds__(kProbeThreads, 1) bench_probe_mix_kernel(float* out, int iters, int pattern) {
     __shared__ __attribute__((aligned(16))) char lds[kProbeMixLds];
     uint32_t h = (blockIdx.x * kProbeThreads + threadIdx.x) * 2654435761u + 12345u;
     auto next_pair = [&]() -> uint32_t {
@@ -124,3 +128,22 @@ __global__ void __launch_bounds__(kProbeThreads, 1) hyd_probe_mix_kernel(float* 
 }
 
 }  // namespace hyd
+
+// Runs one probe launch on the null stream, timed with HIP events.  device_out: device,
+// float[workgroups * 512].  Returns 0, or 1 (bad argument), 2 (HIP error).
+extern "C" int bench_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops, float* ms) {
+    using namespace hyd;
+    if (!device_out || !flops || !ms || workgroups <= 0 || iters <= 0 || pattern < 0 || pattern > 3) return 1;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return 2;
+    (void)hipEventRecord(e0, nullptr);
+    if (pattern < 2) hipLaunchKernelGGL(bench_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, nullptr, device_out, iters, pattern);
+    else hipLaunchKernelGGL(bench_probe_mix_kernel, dim3(workgroups), dim3(kProbeThreads), 0, nullptr, device_out, iters, pattern - 2);
+    (void)hipEventRecord(e1, nullptr);
+    const bool ok = hipGetLastError() == hipSuccess && hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(ms, e0, e1) == hipSuccess;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *flops = (double)workgroups * (kProbeThreads / 64) * (double)iters * (pattern < 2 ? kProbeMfmaPerIter : kProbeMixMfmaPerIter) *
+             (2.0 * 32 * 32 * 16);
+    return ok ? 0 : 2;
+}

@@ -7,13 +7,16 @@ GPU can show exactly one rank's share at its real shape: this module times, thro
 variants of the library, every visit of one rank - forward and backward - and the log-sum-exp
 merges between them.  Prints one JSON object.
 
-    python -m paper_2412_07894_amd.cp_study --config 5 --cp 4
-    python -m paper_2412_07894_amd.cp_study --config 5 --cp 4 --all-ranks [--zigzag]
+    python cp_study.py --config 5 --cp 4
+    python cp_study.py --config 5 --cp 4 --all-ranks [--zigzag]
 """
 import argparse
 import json
 import statistics
+import os
 import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def chunk_ranges(lengths, cp, align):
@@ -48,7 +51,7 @@ def visit_pairs(lengths, bounds, r, c):
 def rank_visits(cid, cp, rank, reps=5, warmup=2):
     import numpy as np
     import torch
-    from . import binding, workloads as wl
+    from paper_2412_07894_amd import binding, workloads as wl
     cfg = wl.CONFIGS[cid]
     lengths = [int(l) for l in wl.seqlens(cid)]
     cu_np = wl.cu_seqlens(lengths)
@@ -112,7 +115,7 @@ def rank_totals(cid, cp, zigzag, reps=3, warmup=1):
     """Kernel time of everything a rank computes (forward, merge, dK/dV, dQ of all its visits), for
     every rank of the CP group in turn on the one GPU."""
     import torch
-    from . import binding, workloads as wl
+    from paper_2412_07894_amd import binding, workloads as wl
     cfg = wl.CONFIGS[cid]
     lengths = [int(l) for l in wl.seqlens(cid)]
     cu_np = wl.cu_seqlens(lengths)

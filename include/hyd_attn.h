@@ -240,26 +240,6 @@ int  hyd_kernel_times(const char** names, float* ms, int cap);
  */
 void hyd_set_wg_trace(void* device_records, int capacity_records);
 
-/*
- * Sustained-rate probe of the bf16 matrix pipe, for putting the roofline fraction of the kernels
- * above into context: enqueues ONE kernel of `workgroups` workgroups (8 waves each, two per
- * SIMD) that issues `iters` x 4 v_mfma_f32_32x32x16_bf16 per wave on register operands and does
- * nothing else.  pattern 0: all operands zero; pattern 1: pseudo-random values of magnitude
- * around one (the sustained clock of the board depends on how many operand bits toggle).
- * patterns 2 and 3 (zeros / random): the same matrix instruction inside the forward kernel's
- * steady-state instruction mix and nothing else - `iters` x 16 MFMAs per wave, each fed by a 1 KB
- * operand fragment read from LDS, and per pair of MFMAs two multiply-adds, two exponentials, one
- * packed conversion, one row-sum dot product and one three-way maximum; no barriers, no memory
- * loads, no masks: the rate the tile loop would reach if all of its synchronisation were free.
- *   device_out   device, float[workgroups * 512], overwritten (keeps the result live)
- *   flops        host, out: floating-point operations the launch performs
- * Time it with the kernel timing hook above (name "probe_mfma") or with events on `hip_stream`.
- * Errors: HYD_ERR_NULL, HYD_ERR_SHAPE (non-positive sizes, unknown pattern), HYD_ERR_ARCH,
- * HYD_ERR_LAUNCH.
- */
-hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops,
-                          void* hip_stream);
-
 #ifdef __cplusplus
 }
 #endif

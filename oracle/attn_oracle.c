@@ -32,7 +32,8 @@
  * Pins (tests/test_oracle_pins.py): full-matrix brute force in numpy, packed == unpacked,
  * softmax rows summing to one, length-1 sequences, uniform-attention closed forms, constant-V,
  * key-shift invariance, causality, GQA == MHA with replicated KV, finite differences,
- * linearity in V and dO.
+ * linearity in V and dO; the backward given stored forward results: equal to the plain backward
+ * on the exact O and LSE, brute force with perturbed O and LSE, closed forms of both perturbations.
  */
 #include <math.h>
 #include <stdint.h>
@@ -85,6 +86,38 @@ static void attn_bwd_one(const double* q, const double* k, const double* v, cons
         double D = 0.0;
         for (int j = 0; j <= i; ++j) { ds[j] = dot(do_i, v + (size_t)j * d, d); D += p[j] * ds[j]; }
         for (int j = 0; j <= i; ++j) ds[j] = p[j] * (ds[j] - D);
+        double* dq_i = dq + (size_t)i * d;
+        for (int c = 0; c < d; ++c) dq_i[c] = 0.0;
+        for (int j = 0; j <= i; ++j) {
+            for (int c = 0; c < d; ++c) {
+                dq_i[c] += scale * ds[j] * k[(size_t)j * d + c];
+                dk[(size_t)j * d + c] += scale * ds[j] * q_i[c];
+                dv[(size_t)j * d + c] += p[j] * do_i[c];
+            }
+        }
+    }
+}
+
+/* The backward as a function of what a backward CALL is given.  A training step runs the forward
+ * first, stores O (in the storage format, e.g. rounded to bf16) and LSE, and hands both to the
+ * backward (the paper's unit of work is one forward and one backward propagation over a buffer,
+ * Sec. 6.1), which does not recompute them: with o_in, lse_in[L] as given,
+ *     P_ij = exp(s_ij - lse_in_i),   D_i = <dO_i, o_in_i>,
+ * and then dS, dQ, dK, dV exactly as in attn_bwd_one.  With the exact O and LSE this IS
+ * attn_bwd_one (P_ij = exp(s_ij - LSE_i) and D_i = sum_j P_ij dP_ij = <dO_i, O_i>); with a rounded
+ * O it tells how much of a difference to the definition is owed to that rounding alone, i.e. to
+ * the interface and not to the arithmetic of the implementation under test. */
+static void attn_bwd_one_given(const double* q, const double* k, const double* v, const double* d_o,
+                               const double* o_in, const double* lse_in, int L, int d, double scale,
+                               double* dq, double* dk, double* dv, double* p, double* ds) {
+    for (int i = 0; i < L; ++i) {
+        const double* q_i = q + (size_t)i * d;
+        const double* do_i = d_o + (size_t)i * d;
+        const double D = dot(do_i, o_in + (size_t)i * d, d);
+        for (int j = 0; j <= i; ++j) {
+            p[j] = exp(scale * dot(q_i, k + (size_t)j * d, d) - lse_in[i]);
+            ds[j] = p[j] * (dot(do_i, v + (size_t)j * d, d) - D);
+        }
         double* dq_i = dq + (size_t)i * d;
         for (int c = 0; c < d; ++c) dq_i[c] = 0.0;
         for (int j = 0; j <= i; ++j) {
@@ -172,6 +205,50 @@ int hyd_oracle_bwd(const float* q, const float* k, const float* v, const float* 
                 unpack(q, hq, d, row0, L, h, qs);
                 unpack(d_o, hq, d, row0, L, h, dos);
                 attn_bwd_one(qs, ks, vs, dos, L, d, scale, dqs, dks, dvs, p, ds);
+                for (int i = 0; i < L; ++i)
+                    memcpy(dq + ((size_t)(row0 + i) * hq + h) * d, dqs + (size_t)i * d, sizeof(double) * d);
+            }
+            for (int i = 0; i < L; ++i) {
+                memcpy(dk + ((size_t)(row0 + i) * hkv + g) * d, dks + (size_t)i * d, sizeof(double) * d);
+                memcpy(dv + ((size_t)(row0 + i) * hkv + g) * d, dvs + (size_t)i * d, sizeof(double) * d);
+            }
+            free(buf);
+        }
+    }
+    return fail ? -2 : 0;
+}
+
+/* Packed backward given the stored forward results o_in[T][Hq][d] and lse_in[Hq][T] (float, the
+ * values the backward call receives); see attn_bwd_one_given.  Outputs as hyd_oracle_bwd. */
+int hyd_oracle_bwd_given(const float* q, const float* k, const float* v, const float* d_o,
+                         const float* o_in, const float* lse_in, const int32_t* cu, int nseq, int T,
+                         int hq, int hkv, int d, double scale, double* dq, double* dk, double* dv) {
+    if (hq <= 0 || hkv <= 0 || hq % hkv || d <= 0 || !check_cu(cu, nseq, T)) return -1;
+    const int G = hq / hkv;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int s = 0; s < nseq; ++s) {
+        for (int g = 0; g < hkv; ++g) {
+            const int row0 = cu[s], L = cu[s + 1] - cu[s];
+            if (L == 0) continue;
+            const size_t n = (size_t)L * d;
+            double* buf = (double*)malloc(sizeof(double) * (8 * n + 3 * (size_t)L));
+            if (!buf) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            double *qs = buf, *ks = qs + n, *vs = ks + n, *dos = vs + n, *os = dos + n, *dqs = os + n,
+                   *dks = dqs + n, *dvs = dks + n, *p = dvs + n, *ds = p + L, *ls = ds + L;
+            unpack(k, hkv, d, row0, L, g, ks);
+            unpack(v, hkv, d, row0, L, g, vs);
+            for (size_t e = 0; e < n; ++e) { dks[e] = 0.0; dvs[e] = 0.0; }
+            for (int h = g * G; h < (g + 1) * G; ++h) {
+                unpack(q, hq, d, row0, L, h, qs);
+                unpack(d_o, hq, d, row0, L, h, dos);
+                unpack(o_in, hq, d, row0, L, h, os);
+                for (int i = 0; i < L; ++i) ls[i] = (double)lse_in[(size_t)h * T + row0 + i];
+                attn_bwd_one_given(qs, ks, vs, dos, os, ls, L, d, scale, dqs, dks, dvs, p, ds);
                 for (int i = 0; i < L; ++i)
                     memcpy(dq + ((size_t)(row0 + i) * hq + h) * d, dqs + (size_t)i * d, sizeof(double) * d);
             }

@@ -31,7 +31,7 @@ def _load():
     global _lib
     if _lib is None:
         _lib = ctypes.CDLL(build())
-        for name in ("hyd_oracle_fwd", "hyd_oracle_bwd", "hyd_oracle_rows", "hyd_oracle_cols",
+        for name in ("hyd_oracle_fwd", "hyd_oracle_bwd", "hyd_oracle_bwd_given", "hyd_oracle_rows", "hyd_oracle_cols",
                      "hyd_oracle_probs", "hyd_oracle_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
@@ -84,6 +84,23 @@ def bwd(q, k, v, d_o, cu_seqlens, scale):
                                 ctypes.c_double(scale), pdq, pdk, pdv)
     if rc:
         raise ValueError(f"hyd_oracle_bwd failed: {rc}")
+    return dq, dk, dv
+
+
+def bwd_given(q, k, v, d_o, o_in, lse_in, cu_seqlens, scale):
+    """The backward as a function of what a backward call receives: the stored forward results
+    o_in[T,Hq,d] (e.g. rounded to bf16) and lse_in[Hq,T] are used as given (P = exp(s - lse_in),
+    D = <dO, o_in>) -> dQ, dK, dV, float64."""
+    T, hq, hkv, d = _dims(q, k)
+    q, pq = _f32(q); k, pk = _f32(k); v, pv = _f32(v); d_o, pdo = _f32(d_o)
+    o_in, po = _f32(o_in); lse_in, pl = _f32(lse_in)
+    assert o_in.shape == (T, hq, d) and lse_in.shape == (hq, T)
+    cu, pcu = _i32(cu_seqlens)
+    dq, pdq = _out((T, hq, d)); dk, pdk = _out((T, hkv, d)); dv, pdv = _out((T, hkv, d))
+    rc = _load().hyd_oracle_bwd_given(pq, pk, pv, pdo, po, pl, pcu, len(cu) - 1, T, hq, hkv, d,
+                                      ctypes.c_double(scale), pdq, pdk, pdv)
+    if rc:
+        raise ValueError(f"hyd_oracle_bwd_given failed: {rc}")
     return dq, dk, dv
 
 

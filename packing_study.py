@@ -7,20 +7,23 @@ micro-batch times (PP - 1 + V), V enumerated), then run every micro-batch of bot
 GPU and compare predicted with measured times.  With --dispatch the draw is first dispatched over
 four simulated pipelines (Sec. 6.2, Alg. 1 against length buckets).  Prints one JSON object.
 
-    python -m paper_2412_07894_amd.packing_study --config 5 --pp 4
-    python -m paper_2412_07894_amd.packing_study --config 3 --pp 4 --dispatch
+    python packing_study.py --config 5 --pp 4
+    python packing_study.py --config 3 --pp 4 --dispatch
 """
 import argparse
 import json
 import statistics
+import os
 import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def time_lengths(lengths, hq, hkv, d, reps, warmup, seed=0):
     """Median milliseconds of one forward + backward over one packed buffer holding `lengths`."""
     import numpy as np
     import torch
-    from . import binding, workloads as wl
+    from paper_2412_07894_amd import binding, workloads as wl
     cu_np = wl.cu_seqlens(lengths)
     T, ml = int(cu_np[-1]), int(max(lengths))
     g = torch.Generator(device="cuda")
@@ -54,7 +57,7 @@ def calibrate(hq, hkv, d, probe_lengths, cap, reps=5, warmup=2):
     sequence of length l is taken inside a packed buffer, as it will run: a buffer of
     k = cap // l copies is timed and divided by k, so that what is paid once per call (launches,
     the schedule prelude) is not charged to every sequence."""
-    from . import planner
+    from paper_2412_07894_amd import planner
     times = []
     for l in probe_lengths:
         k = max(1, int(cap) // int(l))
@@ -75,7 +78,7 @@ def util_len(model, max_len, threshold=0.85):
 
 
 def study(lengths, hq, hkv, d, max_len, pp, probe_lengths, reps=5, warmup=2, node_limit=2_000_000):
-    from . import planner
+    from paper_2412_07894_amd import planner
     model, probe_ms = calibrate(hq, hkv, d, probe_lengths, max_len, reps, warmup)
     # what one call costs before any sequence does: launches and the schedule prelude.  Eq. 1 does
     # not price it (its T(l) is per sequence); it is added to the predictions below so that they
@@ -113,7 +116,7 @@ def dispatch_study(lengths, hq, hkv, d, max_lens, pps, trials, probe_lengths, re
     tightest pipeline that admits it: the naive approach of Sec. 6.2), packs each pipeline's share
     by Eq. 1, runs every micro-batch and prices a pipeline at max micro-batch time x (PP-1+V)."""
     import random
-    from . import planner
+    from paper_2412_07894_amd import planner
     D = len(max_lens)
     assert all(max_lens[j] >= max_lens[j + 1] for j in range(D - 1))
     model, probe_ms = calibrate(hq, hkv, d, probe_lengths, max_lens[0], reps, warmup)
@@ -146,7 +149,7 @@ def dispatch_study(lengths, hq, hkv, d, max_lens, pps, trials, probe_lengths, re
 
 
 def main():
-    from . import workloads as wl
+    from paper_2412_07894_amd import workloads as wl
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--pp", type=int, default=4)

@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "hyd_status_string", "hyd_varlen_attn_workspace_bytes", "hyd_varlen_attn_fwd",
     "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
-    "hyd_probe_mfma", "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
+    "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
 )
 RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
@@ -61,8 +61,6 @@ def load():
     lib.hyd_kernel_times.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float), i]
     lib.hyd_set_wg_trace.restype = None
     lib.hyd_set_wg_trace.argtypes = [vp, i]
-    lib.hyd_probe_mfma.restype = i
-    lib.hyd_probe_mfma.argtypes = [i, i, i, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -252,14 +250,3 @@ def set_wg_trace(records):
     else:
         assert records.dtype == torch.int64 and records.is_contiguous() and records.shape[1] == 4
         load().hyd_set_wg_trace(records.data_ptr(), records.shape[0])
-
-
-def probe_mfma(workgroups, iters, pattern, out=None):
-    """Enqueue the matrix-pipe rate probe on the current stream; returns (flops, out tensor)."""
-    if out is None:
-        out = torch.empty(workgroups * 512, dtype=torch.float32, device="cuda")
-    assert out.dtype == torch.float32 and out.is_contiguous() and out.numel() >= workgroups * 512
-    flops = ctypes.c_double(0.0)
-    _check(load().hyd_probe_mfma(int(workgroups), int(iters), int(pattern), out.data_ptr(),
-                                 ctypes.byref(flops), torch.cuda.current_stream().cuda_stream))
-    return flops.value, out

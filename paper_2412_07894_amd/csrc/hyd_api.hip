@@ -13,7 +13,6 @@
 #include "hyd_fp32.h"
 #include "hyd_fwd_bf16.h"
 #include "hyd_merge.h"
-#include "hyd_probe.h"
 #include "hyd_rope.h"
 
 namespace {
@@ -24,12 +23,15 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace: one or two schedules (the backward has one per tile size when its two kernels use
-// different tiles), then the backward's two float vectors.
+// different tiles), then the backward's row statistics ([Hq][T] floats; the fp32 path uses the
+// first one only) and, for bf16, the fp16 copies of Q, dO and K that its tile loops stream.
+constexpr int kBwdStatVecs = 5;
+constexpr int kHdrAbsmax = 40;            // header word of the dK/dV schedule that holds max |dO| (see BwdScratch)
 struct SchedLayout { size_t hdr, lev, order, items; int n_lev, max_items; };
 struct WsLayout {
     SchedLayout sched[2];
     int n_sched;
-    size_t dvec, lse2vec, total;
+    size_t stat[kBwdStatVecs], q16, do16, k16, total;
 };
 
 size_t sched_layout(SchedLayout& v, size_t at, int T, int nseq, int tile) {
@@ -43,16 +45,21 @@ size_t sched_layout(SchedLayout& v, size_t at, int T, int nseq, int tile) {
     return at;
 }
 
-WsLayout ws_layout(int T, int nseq, int tile0, int tile1, int hq, bool bwd) {
+WsLayout ws_layout(int T, int nseq, int tile0, int tile1, int hq, int hkv, int head_dim, hyd_dtype dt, bool bwd) {
     WsLayout w;
     size_t at = sched_layout(w.sched[0], 0, T, nseq, tile0);
     w.n_sched = tile1 != tile0 ? 2 : 1;
     if (w.n_sched == 2) at = sched_layout(w.sched[1], at, T, nseq, tile1);
     else w.sched[1] = w.sched[0];
-    w.dvec = at;
-    if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
-    w.lse2vec = at;
-    if (bwd) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
+    const int n_stat = !bwd ? 0 : (dt == HYD_BF16 ? kBwdStatVecs : 1);
+    for (int i = 0; i < kBwdStatVecs; ++i) {
+        w.stat[i] = at;
+        if (i < n_stat) at += align_up(sizeof(float) * (size_t)T * (size_t)hq);
+    }
+    const bool copies = bwd && dt == HYD_BF16;
+    w.q16 = at;  if (copies) at += align_up(2 * (size_t)T * (size_t)hq * (size_t)head_dim);
+    w.do16 = at; if (copies) at += align_up(2 * (size_t)T * (size_t)hq * (size_t)head_dim);
+    w.k16 = at;  if (copies) at += align_up(2 * (size_t)T * (size_t)hkv * (size_t)head_dim);
     w.total = at;
     return w;
 }
@@ -248,7 +255,7 @@ const char* hyd_status_string(hyd_status st) {
         case HYD_ERR_SHAPE: return "HYD_ERR_SHAPE: negative size or max_seqlen out of range";
         case HYD_ERR_DTYPE: return "HYD_ERR_DTYPE: unknown dtype";
         case HYD_ERR_HEADS: return "HYD_ERR_HEADS: hq and hkv must be positive with hq % hkv == 0";
-        case HYD_ERR_HEADDIM: return "HYD_ERR_HEADDIM: head_dim must be 128 (bf16) or 64/128 (fp32)";
+        case HYD_ERR_HEADDIM: return "HYD_ERR_HEADDIM: head_dim must be 64 or 128";
         case HYD_ERR_SEQLENS: return "HYD_ERR_SEQLENS: cu_seqlens must start at 0, end at T and not decrease";
         case HYD_ERR_WORKSPACE: return "HYD_ERR_WORKSPACE: workspace NULL, misaligned or too small";
         case HYD_ERR_ARCH: return "HYD_ERR_ARCH: device is not gfx950";
@@ -263,8 +270,8 @@ size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, i
                                        hyd_dtype dt, int is_bwd) {
     if (total_tokens < 0 || num_seqs < 0 || hq <= 0 || hkv <= 0 || hq % hkv != 0) return 0;
     if ((dt != HYD_BF16 && dt != HYD_FP32) || !head_dim_ok(dt, head_dim)) return 0;
-    return (is_bwd ? ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, true)
-                   : ws_layout(total_tokens, num_seqs, tile_fwd(dt), tile_fwd(dt), hq, false)).total;
+    return (is_bwd ? ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, hkv, head_dim, dt, true)
+                   : ws_layout(total_tokens, num_seqs, tile_fwd(dt), tile_fwd(dt), hq, hkv, head_dim, dt, false)).total;
 }
 
 }  // extern "C"
@@ -294,7 +301,7 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     const int tile = tile_fwd(dt);
-    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, tile, hq, false);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile, tile, hq, hkv, head_dim, dt, false);
     const SchedView sv = make_view(static_cast<char*>(workspace), w.sched[0], tile, max_seqlen);
     {
         KernelTimer kt("schedule_prelude", st);
@@ -354,12 +361,11 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     if (ds != HYD_OK) return ds;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
-    const WsLayout w = ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, true);
+    const WsLayout w = ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, hkv, head_dim, dt, true);
     char* ws = static_cast<char*>(workspace);
     const SchedView sv_kv = make_view(ws, w.sched[0], tile_kv(dt), max_seqlen);
     const SchedView sv_q = make_view(ws, w.sched[1], tile_dq(dt), max_seqlen);
-    float* Dvec = reinterpret_cast<float*>(ws + w.dvec);
-    float* Lse2 = reinterpret_cast<float*>(ws + w.lse2vec);
+    float* Dvec = reinterpret_cast<float*>(ws + w.stat[0]);
     // one launch builds the item list of the dK/dV kernel and, if the dQ kernel uses another tile
     // size, the dQ kernel's too (one workgroup each)
     {
@@ -370,20 +376,38 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     const long long n_rows = (long long)total_tokens * hq;
     const long long work_q = (long long)sv_q.max_items * hq, work_kv = (long long)sv_kv.max_items * hkv;
     if (dt == HYD_BF16) {
+        BwdScratch sc;
+        sc.Dq = Dvec;
+        sc.lse2q = reinterpret_cast<float*>(ws + w.stat[1]);
+        sc.kqmul = reinterpret_cast<float*>(ws + w.stat[2]);
+        sc.lse2kv = reinterpret_cast<float*>(ws + w.stat[3]);
+        sc.Dkv = reinterpret_cast<float*>(ws + w.stat[4]);
+        sc.absmax = reinterpret_cast<uint32_t*>(sv_kv.hdr + kHdrAbsmax);      // the prelude has cleared the header
+        sc.q16 = reinterpret_cast<uint16_t*>(ws + w.q16);
+        sc.do16 = reinterpret_cast<uint16_t*>(ws + w.do16);
+        sc.k16 = reinterpret_cast<uint16_t*>(ws + w.k16);
+        const dim3 rgrid((unsigned)((n_rows + 15) / 16));
         {
-            KernelTimer kt("bwd_rowdot_bf16", st);
-            const dim3 rgrid((unsigned)((n_rows + 15) / 16));
+            KernelTimer kt("bwd_rowstats_bf16", st);
             if (head_dim == 64)
-                hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2, total_tokens, hq);
+                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, sc, total_tokens, hq);
             else
-                hipLaunchKernelGGL(hyd_bwd_rowdot_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, Dvec, Lse2, total_tokens, hq);
+                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, sc, total_tokens, hq);
+        }
+        {
+            KernelTimer kt("bwd_convert_bf16", st);
+            if (head_dim == 64)
+                hipLaunchKernelGGL(hyd_bwd_convert_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+                                   static_cast<const uint16_t*>(d_o), static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
+            else
+                hipLaunchKernelGGL(hyd_bwd_convert_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+                                   static_cast<const uint16_t*>(d_o), static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
         }
         BwdParams p;
-        p.q = static_cast<const uint16_t*>(q); p.k = static_cast<const uint16_t*>(k);
         p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
-        p.lse2 = Lse2; p.D = Dvec;
+        p.sc = sc;
         p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
         p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
@@ -565,26 +589,6 @@ int hyd_kernel_times(const char** names, float* ms, int cap) {
 void hyd_set_wg_trace(void* device_records, int capacity_records) {
     t_trace.rec = static_cast<unsigned long long*>(device_records);
     t_trace.capacity = device_records ? capacity_records : 0;
-}
-
-hyd_status hyd_probe_mfma(int workgroups, int iters, int pattern, float* device_out, double* flops, void* hip_stream) {
-    if (!device_out || !flops) return HYD_ERR_NULL;
-    if (workgroups <= 0 || iters <= 0 || pattern < 0 || pattern > 3) return HYD_ERR_SHAPE;
-    DeviceInfo* dev = nullptr;
-    const hyd_status st_dev = device_info(&dev);
-    if (st_dev != HYD_OK) return st_dev;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    {
-        KernelTimer kt("probe_mfma", st);
-        if (pattern < 2)
-            hipLaunchKernelGGL(hyd_probe_mfma_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern);
-        else
-            hipLaunchKernelGGL(hyd_probe_mix_kernel, dim3(workgroups), dim3(kProbeThreads), 0, st, device_out, iters, pattern - 2);
-    }
-    if (hipGetLastError() != hipSuccess) return HYD_ERR_LAUNCH;
-    *flops = (double)workgroups * (kProbeThreads / 64) * (double)iters * (pattern < 2 ? kProbeMfmaPerIter : kProbeMixMfmaPerIter) *
-             (2.0 * 32 * 32 * 16);
-    return HYD_OK;
 }
 
 }  // extern "C"

@@ -1,5 +1,17 @@
-// bf16 backward kernels: D = rowsum(dO * O), dK/dV, and dQ.  No atomics: every output element has
-// exactly one producing wave with a fixed summation order, so results are bitwise reproducible.
+// bf16 backward kernels: row statistics and fp16 operand copies, dK/dV, and dQ.  No atomics on
+// results: every output element has exactly one producing wave with a fixed summation order, so
+// results are bitwise reproducible (the one atomic, a maximum over |dO|, does not depend on order).
+//
+// Arithmetic.  The four products that consume a factor formed in registers (dV = P^T dO,
+// dK = dS^T Q, dQ = dS K) and the products next to them run on the fp16 MFMA: P and dS keep 11
+// significant bits instead of the 8 that bf16 would leave them, which is what an absolute error
+// bar of 2e-2 on gradients of size 4-8 needs (their own rounding to bf16 already takes 1.6e-2 of
+// it).  Every bf16 input converts to fp16 exactly as long as its magnitude lies in [2^-14, 65504];
+// dO, whose scale is arbitrary (it is linear in the loss), is brought into that range by powers
+// of two: one per tensor for dK/dV (sums over rows need a common scale), one per row for dQ
+// (folded into the row's -LSE2, so that it costs nothing), both undone when the results are
+// written.  The fp16 copies of Q, K and dO that the tile loops stream are written once per call
+// into the workspace.
 //
 // Fragment convention (see hyd_device.h): an MFMA operand fragment is "lane <-> one index, 8
 // register slots <-> contraction index" and can be used as the A or the B operand alike; the
@@ -12,44 +24,120 @@
 
 namespace hyd {
 
-// ---------------------------------------------------------------------------------------------
-// D[h][t] = sum_c dO[t][h][c] * O[t][h][c]  (fp32) and LSE2 = LSE * log2(e), both stored NEGATED:
-// the form in which the two backward kernels consume them (P = exp2(s * scale * log2(e) + (-LSE2)),
-// dS = P * (dP + (-D))), so that dK/dV can use them as initial values of its score and dP
-// accumulators.  16 lanes per row.
-// ---------------------------------------------------------------------------------------------
 constexpr float kLog2e = 1.44269504088896340736f;
 
+// Power-of-two exponent k that brings a magnitude (given by the 15 low bits of its bf16 pattern)
+// into [1, 2): |x| * 2^k.  Zero, subnormal, infinite and NaN magnitudes give 0; |k| <= kMaxShift
+// keeps 2^k, 2^-k and P * 2^k inside fp32.
+constexpr int kMaxShift = 100;
+__device__ __forceinline__ int shift_of(uint32_t abs_bf16) {
+    const int e = (int)(abs_bf16 >> 7);                  // biased exponent
+    if (e == 0 || e == 255) return 0;
+    const int k = 127 - e;
+    return k > kMaxShift ? kMaxShift : (k < -kMaxShift ? -kMaxShift : k);
+}
+__device__ __forceinline__ float pow2i(int k) { return __uint_as_float((uint32_t)(127 + k) << 23); }
+
+// Row statistics and scratch of the backward, all in the caller's workspace.
+struct BwdScratch {
+    float* Dq;          // [Hq][T]  -D,  D = rowsum(dO * O)                          (dQ kernel)
+    float* lse2q;       // [Hq][T]  -LSE * log2(e) + kq, kq = shift_of(row max |dO|) (dQ kernel: P * 2^kq)
+    float* kqmul;       // [Hq][T]  2^-kq                                            (dQ kernel's epilogue)
+    float* lse2kv;      // [Hq][T]  -LSE * log2(e)                                   (dK/dV kernel)
+    float* Dkv;         // [Hq][T]  -D * 2^kg, kg = shift_of(max |dO| of the tensor) (dK/dV kernel)
+    uint32_t* absmax;   // max over dO of the 15-bit magnitude pattern; zeroed by the schedule prelude
+    uint16_t* q16;      // [T][Hq][d]  fp16 copy of Q
+    uint16_t* do16;     // [T][Hq][d]  fp16 copy of dO * 2^kg
+    uint16_t* k16;      // [T][Hkv][d] fp16 copy of K
+};
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1 over O and dO (16 lanes per row): the row statistics above except Dkv, and the tensor's
+// largest |dO|.  The statistics are stored NEGATED: the form in which the two backward kernels
+// consume them (P = exp2(s * scale * log2(e) + (-LSE2)), dS = P * (dP + (-D))), so that dK/dV can
+// use -D as the initial value of its dP accumulator.
+// ---------------------------------------------------------------------------------------------
 template <int HD = kHeadDim>
-__global__ void __launch_bounds__(256) hyd_bwd_rowdot_bf16_kernel(const uint16_t* __restrict__ o,
-                                                                 const uint16_t* __restrict__ d_o,
-                                                                 const float* __restrict__ lse,
-                                                                 float* __restrict__ D, float* __restrict__ lse2,
-                                                                 int T, int hq) {
+__global__ void __launch_bounds__(256) hyd_bwd_rowstats_bf16_kernel(const uint16_t* __restrict__ o,
+                                                                   const uint16_t* __restrict__ d_o,
+                                                                   const float* __restrict__ lse,
+                                                                   BwdScratch sc, int T, int hq) {
     const int64_t n_rows = (int64_t)T * hq;
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
     float acc = 0.f;
+    uint32_t amax = 0;
     if (row < n_rows && (HD == kHeadDim || c < HD / 8)) {
         const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + c * 8);
         const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + row * HD + c * 8);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
+        for (int e = 0; e < 4; ++e) {
+            acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
+            amax = max(amax, max(b[e] & 0x7fffu, (b[e] >> 16) & 0x7fffu));
+        }
     }
-    acc += __shfl_xor(acc, 1, 64);
-    acc += __shfl_xor(acc, 2, 64);
-    acc += __shfl_xor(acc, 4, 64);
-    acc += __shfl_xor(acc, 8, 64);
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) {
+        acc += __shfl_xor(acc, m, 64);
+        amax = max(amax, (uint32_t)__shfl_xor((int)amax, m, 64));
+    }
     if (row < n_rows && c == 0) {
         const int t = (int)(row / hq), h = (int)(row % hq);
-        D[(int64_t)h * T + t] = -acc;
-        lse2[(int64_t)h * T + t] = -lse[(int64_t)h * T + t] * kLog2e;
+        const int64_t at = (int64_t)h * T + t;
+        const int kq = shift_of(amax);
+        const float l2 = -lse[at] * kLog2e;
+        sc.Dq[at] = -acc;
+        sc.lse2q[at] = l2 + (float)kq;
+        sc.kqmul[at] = pow2i(-kq);
+        sc.lse2kv[at] = l2;
+    }
+    // the tensor's maximum: one atomic per wave at most, and none once the stored value has caught
+    // up (the plain read only filters; the atomic decides)
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 16, 64));
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32, 64));
+    if ((threadIdx.x & 63) == 0 && amax > __hip_atomic_load(sc.absmax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(sc.absmax, amax);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2 (16 lanes per row): the fp16 copies of Q, dO * 2^kg and K, and Dkv = -D * 2^kg.
+// ---------------------------------------------------------------------------------------------
+template <int HD = kHeadDim>
+__global__ void __launch_bounds__(256) hyd_bwd_convert_bf16_kernel(const uint16_t* __restrict__ q,
+                                                                  const uint16_t* __restrict__ d_o,
+                                                                  const uint16_t* __restrict__ k,
+                                                                  BwdScratch sc, int T, int hq, int hkv) {
+    const int64_t n_rows = (int64_t)T * hq, n_kv = (int64_t)T * hkv;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c = threadIdx.x & 15;
+    const float up = pow2i(shift_of(*sc.absmax));
+    if (row < n_rows && (HD == kHeadDim || c < HD / 8)) {
+        const int64_t at = row * HD + c * 8;
+        const u32x4 a = *reinterpret_cast<const u32x4*>(q + at);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + at);
+        u32x4 a16, b16;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a16[e] = bf16x2_to_f16x2(a[e]); b16[e] = bf16x2_to_f16x2(b[e], up); }
+        *reinterpret_cast<u32x4*>(sc.q16 + at) = a16;
+        *reinterpret_cast<u32x4*>(sc.do16 + at) = b16;
+        if (row < n_kv) {
+            const u32x4 x = *reinterpret_cast<const u32x4*>(k + at);
+            u32x4 x16;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x16[e] = bf16x2_to_f16x2(x[e]);
+            *reinterpret_cast<u32x4*>(sc.k16 + at) = x16;
+        }
+    }
+    if (row < n_rows && c == 0) {
+        const int t = (int)(row / hq), h = (int)(row % hq);
+        const int64_t at = (int64_t)h * T + t;
+        sc.Dkv[at] = sc.Dq[at] * up;
     }
 }
 
 struct BwdParams {
-    const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
-    const float* lse2; const float* D;      // -LSE * log2(e) and -rowsum(dO * O), both [Hq][T]
+    const uint16_t* v; const uint16_t* d_o;     // the caller's bf16 V and dO (Q, K and the scaled dO are read from sc)
+    BwdScratch sc;
     uint16_t* dq; uint16_t* dk; uint16_t* dv;
     int T, hq, hkv;
     float scale, scale_log2;
@@ -64,7 +152,11 @@ struct BwdParams {
 // Same orientation, K/V ring and causal structure as the forward kernel: S^T[key][q] = K Q^T and
 // dP^T[key][q] = V dO^T put one query row in each lane, so LSE_i and D_i are per-lane scalars;
 // dS^T then is the B operand of dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing
-// LDS read of the same K tile.
+// LDS read of the same K tile.  The K tiles are the fp16 copy (score and dQ products on the fp16
+// MFMA, Q rows from the fp16 copy too); V tiles and dO rows are the caller's bf16 tensors (dP on
+// the bf16 MFMA, exact inputs either way).  The row's P carries the factor 2^kq that brings its dO
+// into fp16's range (it sits in -LSE2), so dS = P (dP - D) is formed for the scaled row and dQ is
+// scaled back by 2^-kq when it is written.
 // ---------------------------------------------------------------------------------------------
 constexpr int kDqWaves = 8;
 constexpr int kDqBM = 32 * kDqWaves, kDqBN = 64, kDqThreads = 64 * kDqWaves;
@@ -88,7 +180,7 @@ template <int D>
 __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int kb,
                                          const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], f32x16 (&acc)[D / 32],
                                          float scale_log2, float lse2, float Dq, bool mask, int krel) {
-    // lse2 and Dq hold -LSE2 and -D of the lane's row
+    // lse2 and Dq hold -LSE2 + kq and -D of the lane's row; qf and the K tile are fp16, dof and the V tile bf16
     constexpr int NK = D / 16, NDB = D / 32;
     // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
@@ -109,7 +201,7 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
                 for (int r = 0; r < 16; ++r)
                     if (8 * (r >> 2) + (r & 3) + krel > 0) s[r] = -INFINITY;
             }
-            if (i < NK) s = mfma32(f[i % kAhead], qf[i], s);
+            if (i < NK) s = mfma32h(f[i % kAhead], qf[i], s);
             else dp = mfma32(f[i % kAhead], dof[i - NK], dp);
             if (i + kAhead < 2 * NK) f[i % kAhead] = frag_row(i + kAhead < NK ? Kt : Vt, fa, kb, (i + kAhead) % NK);
             if (i >= NK) {                        // the exponentials of the finished score block run under the dP product
@@ -130,7 +222,7 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     __builtin_amdgcn_sched_barrier(0);
     auto ds_pair = [&](int j) -> uint32_t {   // scores 2j, 2j+1 of the 16 a lane holds
         const int r = 2 * j;
-        return pack_bf16(s[r] * (dp[r] + Dq), s[r + 1] * (dp[r + 1] + Dq));     // s holds P by now
+        return pack_f16(s[r] * (dp[r] + Dq), s[r + 1] * (dp[r + 1] + Dq));      // s holds P * 2^kq by now
     };
     u32x4 dcur, dnxt;
 #pragma unroll
@@ -139,7 +231,7 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
 #pragma unroll
     for (int i = 0; i < 2 * NDB; ++i) {       // i = NDB*b2 + db
         const int b2 = i / NDB, db = i % NDB;
-        acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(dcur), acc[db]);
+        acc[db] = mfma32h(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(dcur), acc[db]);
         if (i + kCAhead < 2 * NDB) issue_col(lq, cf[i % kCAhead], Kt, fa, 2 * kb + (i + kCAhead) / NDB, (i + kCAhead) % NDB);
         if (b2 == 0) {
 #pragma unroll
@@ -220,7 +312,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         const int td = wrow0 / kDqBN;                     // this wave's diagonal (= last) tile
         const int diag_kb = (wrow0 % kDqBN) / 32;         // its diagonal block within that tile
         const uint32_t kv_bytes = (uint32_t)(kv_end - 1) * kv_stride_b + kRowB;
-        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.k + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.sc.k16 + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.v + (int64_t)row0 * kv_stride + (int64_t)g * D, kv_bytes);
         auto dma_tile = [&](int t, int stage) {
             char* dst = smem + stage * kDqStageBytes + 4 * wave * kRowBytes;
@@ -236,15 +328,16 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         {   // rows q0 .. q0+255 of Q and dO of this head; rows past the query range read as zeros
             const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kDqBM) - 1) * q_stride_b + kRowB;
             const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * D;
-            dma_rows<kDqWaves>(make_rsrc(p.q + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
+            dma_rows<kDqWaves>(make_rsrc(p.sc.q16 + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
                                kDqBM / 64, q_stride_b, wave, dma_voff_q);
             dma_rows<kDqWaves>(make_rsrc(p.d_o + off, q_bytes), smem + kDqStageBytes, [](int j) { return j * kDqTileBytes; },
                                kDqBM / 64, q_stride_b, wave, dma_voff_q);
         }
-        float lse2 = 0.f, Dq = 0.f;
+        float lse2 = 0.f, Dq = 0.f, unshift = 0.f;
         if (qvalid) {
-            lse2 = p.lse2[(int64_t)head * p.T + row0 + qrow];
-            Dq = p.D[(int64_t)head * p.T + row0 + qrow];
+            lse2 = p.sc.lse2q[(int64_t)head * p.T + row0 + qrow];
+            Dq = p.sc.Dq[(int64_t)head * p.T + row0 + qrow];
+            unshift = p.sc.kqmul[(int64_t)head * p.T + row0 + qrow];
         }
         f32x16 acc[D / 32];
 #pragma unroll
@@ -300,7 +393,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         }
         if (active)         // dQ leaves through this wave's 8 KB of the ring (free now): whole rows per store
             store_rows_via_lds<D>(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * D, q_stride, Lq - wrow0,
-                               acc, p.scale, o_stage, lane);
+                               acc, p.scale * unshift, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 2, t_start, n_done);
@@ -321,8 +414,10 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
 // S[i][j] and dP[i][j] put one KEY in each lane (accumulator column) and query rows in the slots,
 // so P and dS are directly the B fragments (contraction index = query row) of the second
 // products, whose A fragments come from the transposing LDS read of the dO and Q tiles.  P crosses
-// lane-to-lane (same accumulator layout on both sides) as fp16: half the LDS traffic of fp32 and,
-// unlike bf16, no measurable change in dK.
+// lane-to-lane (same accumulator layout on both sides) as fp16, the form in which role A's own
+// dV product consumes it.  All four products run on the fp16 MFMA: the Q and dO tiles are the
+// fp16 copies (dO scaled by 2^kg), K rows come from the fp16 copy, V rows are converted in
+// registers once per item; dK and dV are scaled back by 2^-kg when they are written.
 // Query tiles of 64 rows (Q, dO, LSE2, D) stream through a ring of 3 LDS stages by
 // direct-to-LDS loads, for every query head of the KV group in turn, accumulating into the same
 // registers.  One workgroup barrier per 32-row block: it publishes P and, every second block,
@@ -378,6 +473,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
     char* const pbuf = smem + kKvPOff + pair * 2 * kKvPBytes + lane * 8;      // + buf * kKvPBytes + q * 512
+    const float unscale = pow2i(-shift_of(*p.sc.absmax));                     // 2^-kg
 
     WorkFetcher wf;
     WorkItem wi;
@@ -419,8 +515,8 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             const int qt = ld_qt;
             if (++ld_h == G) { ld_h = 0; ++ld_qt; }
             const int64_t base = (int64_t)row0 * q_stride + (int64_t)h * D;
-            const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.q + base, q_bytes);
-            const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.d_o + base, q_bytes);
+            const __amdgpu_buffer_rsrc_t rq = make_rsrc(p.sc.q16 + base, q_bytes);
+            const __amdgpu_buffer_rsrc_t rdo = make_rsrc(p.sc.do16 + base, q_bytes);
             char* dst = smem + stage * kKvStageBytes + 4 * wave * kRowBytes;
 #pragma unroll
             for (int j = 0; j < 16 / kKvWaves; ++j) {
@@ -433,7 +529,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             // waves repeat wave 1's load so that all waves count alike); rows past the sequence
             // read as 0, which is harmless because their Q and dO rows are 0 too
             const int which = wave == 0 ? 0 : 1;
-            const float* src = (which == 0 ? p.lse2 : p.D) + (int64_t)h * p.T + row0;
+            const float* src = (which == 0 ? p.sc.lse2kv : p.sc.Dkv) + (int64_t)h * p.T + row0;
             const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, stat_bytes);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + which * kKvBM * 4),
                                                      4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);
@@ -445,7 +541,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             static_assert(kKvBN == 128 && kKvPairs * 2 * kKvPBytes >= kKvBN * kRowBytes, "K/V staging");
             const uint32_t k_bytes = (uint32_t)(min(Lk - j0, kKvBN) - 1) * kv_stride_b + kRowB;
             const int64_t off = (int64_t)(row0 + j0) * kv_stride + (int64_t)g * D;
-            dma_rows<kKvWaves>(make_rsrc(p.k + off, k_bytes), smem + 2 * kKvStageBytes, [](int j) { return j * kKvTileBytes; },
+            dma_rows<kKvWaves>(make_rsrc(p.sc.k16 + off, k_bytes), smem + 2 * kKvStageBytes, [](int j) { return j * kKvTileBytes; },
                                kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
             dma_rows<kKvWaves>(make_rsrc(p.v + off, k_bytes), smem + kKvPOff, [](int j) { return j * kKvTileBytes; },
                                kKvBN / 64, kv_stride_b, wave, dma_voff_kv);
@@ -456,18 +552,24 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
         __syncthreads();                                      // stages 0 and 1 and the K / V rows have landed
-        // this wave's register operand of the first product: K rows (role A) or V rows (role B)
+        // this wave's register operand of the first product: K rows (role A, fp16 already) or V
+        // rows (role B, converted from bf16 here)
         bf16x8 bf[NK];
         {
             u32x4 a[NK];
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) a[ks] = *(lds_u32x4*)(uintptr_t)(fa.row[ks] + kv_stage);
             __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0)
-            const uint32_t flip = role_b ? 0u : sign_flip;
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
                 asm volatile("" : "+v"(a[ks]));               // the reads stay on this side of the barrier
-                bf[ks] = as_bf16x8(a[ks] ^ flip);
+                if (role_b) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[ks][e] = bf16x2_to_f16x2(a[ks][e]);
+                } else {
+                    a[ks] ^= sign_flip;
+                }
+                bf[ks] = as_bf16x8(a[ks]);
             }
         }
         __builtin_amdgcn_s_barrier();                         // stage 2 and the P area may be written now
@@ -512,7 +614,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < NK; ++i) {
-                    x = mfma32(f[i % kAhead], bf[i], x);
+                    x = mfma32h(f[i % kAhead], bf[i], x);
                     if (i + kAhead < NK) f[i % kAhead] = frag_row(T1, fa, ib, i + kAhead);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -530,13 +632,11 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * rq + e], scale_log2, l4r[e]));
-                        pk[2 * rq] = pack_bf16(pv[0], pv[1]);
-                        pk[2 * rq + 1] = pack_bf16(pv[2], pv[3]);
-                        // P crosses to role B as fp16 (11 significant bits, 0.024 % below P on average by
-                        // truncation; the rounding of dS to bf16 that follows is ten times coarser)
-                        const auto h01 = __builtin_amdgcn_cvt_pkrtz(pv[0], pv[1]), h23 = __builtin_amdgcn_cvt_pkrtz(pv[2], pv[3]);
-                        const f16x4 hv = {h01[0], h01[1], h23[0], h23[1]};
-                        *reinterpret_cast<f16x4*>(pbuf + parity * kKvPBytes + rq * 512) = hv;
+                        // one fp16 rounding of P serves both this wave's dV product and role B
+                        pk[2 * rq] = pack_f16(pv[0], pv[1]);
+                        pk[2 * rq + 1] = pack_f16(pv[2], pv[3]);
+                        const u32x2 hv = {pk[2 * rq], pk[2 * rq + 1]};
+                        *reinterpret_cast<u32x2*>(pbuf + parity * kKvPBytes + rq * 512) = hv;
                     }
                 }
                 // the first fragments of the second product are requested BEFORE the barrier (their
@@ -565,8 +665,8 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                         const f16x4 hv = *reinterpret_cast<const f16x4*>(pbuf + parity * kKvPBytes + rq * 512);
                         // written as fused multiply-adds with a zero addend so that the fp16 factor is
                         // converted inside the instruction (v_fma_mix_f32) instead of by one of its own
-                        pk[2 * rq] = pack_bf16(__builtin_fmaf((float)hv[0], x[4 * rq], 0.f), __builtin_fmaf((float)hv[1], x[4 * rq + 1], 0.f));
-                        pk[2 * rq + 1] = pack_bf16(__builtin_fmaf((float)hv[2], x[4 * rq + 2], 0.f), __builtin_fmaf((float)hv[3], x[4 * rq + 3], 0.f));
+                        pk[2 * rq] = pack_f16(__builtin_fmaf((float)hv[0], x[4 * rq], 0.f), __builtin_fmaf((float)hv[1], x[4 * rq + 1], 0.f));
+                        pk[2 * rq + 1] = pack_f16(__builtin_fmaf((float)hv[2], x[4 * rq + 2], 0.f), __builtin_fmaf((float)hv[3], x[4 * rq + 3], 0.f));
                     }
                 }
                 // the bookkeeping of the reads issued before the barrier, restated as constants
@@ -578,7 +678,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
                 for (int i = 0; i < 2 * NDB; ++i) {           // i = NDB*b2 + db
                     const int b2 = i / NDB, db = i % NDB;
                     u32x4 bv = {pk[4 * b2], pk[4 * b2 + 1], pk[4 * b2 + 2], pk[4 * b2 + 3]};
-                    acc[db] = mfma32(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(bv), acc[db]);
+                    acc[db] = mfma32h(lds_wait(lq, cf[i % kCAhead]), as_bf16x8(bv), acc[db]);
                     if (i + kCAhead < 2 * NDB) issue_col(lq, cf[i % kCAhead], T2, fa, 2 * ib + (i + kCAhead) / NDB, (i + kCAhead) % NDB);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -615,7 +715,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
         __syncthreads();                                      // every wave is done with the ring
         if (active)
             store_rows_via_lds<D>((role_b ? p.dk : p.dv) + (int64_t)(row0 + wkey0) * kv_stride + (int64_t)g * D, kv_stride,
-                               Lk - wkey0, acc, role_b ? p.scale : 1.f, o_stage, lane);
+                               Lk - wkey0, acc, (role_b ? p.scale : 1.f) * unscale, o_stage, lane);
         have = wf.next(p.hm, p.cursors, p.items, slot, wi);
     }
     trace_write(p.tr, 1, t_start, n_done);

@@ -12,6 +12,8 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) __fp16 f16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -26,6 +28,18 @@ constexpr int kChunksPerRow = kRowBytes / 16; // 16-byte chunks per row
 //   acc[r] = D[8 * (r / 4) + 4 * half + r % 4][l % 32],             r = 0..15
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// v_mfma_f32_32x32x16_f16: same shape, rate and lane maps, operands in fp16 (11 significant bits).
+// The backward's products run on it: every bf16 input converts to fp16 exactly (magnitudes in
+// [2^-14, 65504]), and the factors formed in registers (P, dS) keep three more bits than bf16
+// would leave them.  Fragments travel as 16-byte register groups typed bf16x8 whatever their
+// element format is; this wrapper reads the bits as fp16.
+__device__ __forceinline__ f32x16 mfma32h(bf16x8 a, bf16x8 b, f32x16 c) {
+    f16x8 x, y;
+    __builtin_memcpy(&x, &a, 16);
+    __builtin_memcpy(&y, &b, 16);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -43,8 +57,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float x, float y) {
     return r;
 }
 
+// Two floats -> packed fp16 pair (round to nearest even, v_cvt_pk_f16_f32), low half = x.
+__device__ __forceinline__ uint32_t pack_f16(float x, float y) {
+    f32x2 v = {x, y};
+    f16x2 h = __builtin_convertvector(v, f16x2);
+    uint32_t r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// Packed bf16 pair -> packed fp16 pair, each value times `mul` (a power of two).  Exact for
+// magnitudes in [2^-14, 65504]; smaller ones keep an absolute accuracy of 2^-25, larger ones
+// become infinite (and NaN stays NaN), so that an input outside the fp16 range shows in the result.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t u, float mul = 1.f) {
+    return pack_f16(bf16_lo(u) * mul, bf16_hi(u) * mul);
+}
 
 // LDS tile of bf16 rows of 256 bytes, no padding.  The 16-byte chunk c of row r lives at chunk
 // position c ^ swz(r).  swz is chosen so that both access patterns of the kernels are free of

@@ -44,3 +44,29 @@ def packed(q, k, v, cu, scale, d_o=None):
             if d_o is not None:
                 dq[a:b, h] = r[3]; dk[a:b, g] += r[4]; dv[a:b, g] += r[5]
     return (o, lse) if d_o is None else (o, lse, dq, dk, dv)
+
+
+def one_head_given(q, k, v, scale, d_o, o_in, lse_in):
+    """Matrix form of the backward that takes the stored forward results as given:
+    P = exp(S - lse_in) below and on the diagonal, D = rowsum(dO * o_in)."""
+    L = q.shape[0]
+    q, k, v, d_o = (x.astype(np.float64) for x in (q, k, v, d_o))
+    p = np.tril(np.exp(scale * (q @ k.T) - np.asarray(lse_in, dtype=np.float64)[:, None]))
+    ds = p * (d_o @ v.T - (d_o * np.asarray(o_in, dtype=np.float64)).sum(axis=1, keepdims=True))
+    return scale * ds @ k, scale * ds.T @ q, p.T @ d_o
+
+
+def packed_given(q, k, v, cu, scale, d_o, o_in, lse_in):
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    G = hq // hkv
+    dq = np.zeros((T, hq, d)); dk = np.zeros((T, hkv, d)); dv = np.zeros((T, hkv, d))
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        for h in range(hq):
+            if a == b:
+                continue
+            g = h // G
+            r = one_head_given(q[a:b, h], k[a:b, g], v[a:b, g], scale, d_o[a:b, h], o_in[a:b, h], lse_in[h, a:b])
+            dq[a:b, h] = r[0]; dk[a:b, g] += r[1]; dv[a:b, g] += r[2]
+    return dq, dk, dv

@@ -169,13 +169,3 @@ def test_status_strings(lib):
     seen = {b.status_string(c) for c in range(12)}
     assert len(seen) == 12 and all(s.startswith("HYD_") for s in seen)
     assert "unknown" in b.status_string(99)
-
-
-def test_probe_argument_errors(lib):
-    flops = ctypes.c_double(0.0)
-    out = ctypes.c_void_p(4096)
-    assert lib.hyd_probe_mfma(256, 100, 1, None, ctypes.byref(flops), None) == 1
-    assert lib.hyd_probe_mfma(256, 100, 1, out, None, None) == 1
-    assert lib.hyd_probe_mfma(0, 100, 1, out, ctypes.byref(flops), None) == 2
-    assert lib.hyd_probe_mfma(256, 0, 1, out, ctypes.byref(flops), None) == 2
-    assert lib.hyd_probe_mfma(256, 100, 7, out, ctypes.byref(flops), None) == 2

@@ -2,7 +2,7 @@
 and partition every sequence; the pair count of a visit equals a brute-force count."""
 import numpy as np
 
-from paper_2412_07894_amd import cp_study
+import cp_study
 
 
 def test_chunk_ranges_partition_and_alignment():

@@ -9,7 +9,7 @@ pytestmark = pytest.mark.gpu
 
 
 def test_balanced_packing_against_max_length_packing():
-    from paper_2412_07894_amd import packing_study as ps
+    import packing_study as ps
     rng = random.Random(4)
     # long-tailed draw (Sec. 3.1: short sequences dominate, long ones are rare), 4 x 32768 tokens
     lengths, cap = [], 4 * 32768
@@ -32,7 +32,7 @@ def test_balanced_packing_against_max_length_packing():
 
 
 def test_greedy_dispatch_against_length_buckets():
-    from paper_2412_07894_amd import packing_study as ps
+    import packing_study as ps
     rng = random.Random(8)
     lengths = []
     # an iteration without very long sequences: the case in which length buckets leave the

@@ -16,11 +16,8 @@ def full_parity(lengths, hq, hkv, d, dtype, seed, scale=None, host_cu=True):
     scale = 1.0 / np.sqrt(d) if scale is None else scale
     print(f"\ncase lengths={list(lengths)[:12]}{'...' if len(lengths) > 12 else ''} hq={hq} hkv={hkv} d={d} {dtype} seed={seed} scale={scale}", flush=True)
     got = gu.run_gpu(cu, q, k, v, do, dtype, scale, host_cu=host_cu)
-    o, lse = orc.fwd(q, k, v, cu, scale)
-    dq, dk, dv = orc.bwd(q, k, v, do, cu, scale)
     failures = []
-    for name, ref in (("o", o), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
-        gu.check(name, got[name], ref, dtype, failures=failures)
+    gu.check_all(got, q, k, v, do, cu, scale, dtype, failures, orc)
     assert not failures, "\n".join(failures)
     return got
 
@@ -126,7 +123,8 @@ def test_backward_alone_with_oracle_forward():
     o, lse = orc.fwd(q, k, v, cu, scale)
     o_b = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(o.astype(np.float32)))
     got = gu.run_gpu(cu, q, k, v, do, "bf16", scale, o_lse=(o_b, lse))
-    dq, dk, dv = orc.bwd(q, k, v, do, cu, scale)
+    # the reference is the oracle's backward of exactly what the GPU backward was handed
+    dq, dk, dv = orc.bwd_given(q, k, v, do, o_b, lse.astype(np.float32), cu, scale)
     for name, ref in (("dq", dq), ("dk", dk), ("dv", dv)):
         gu.check(name, got[name], ref, "bf16")
 

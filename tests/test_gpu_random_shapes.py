@@ -35,11 +35,8 @@ def test_random_shape(seed):
     print(f"\nrandom shape seed={seed} lengths={lengths} hq={hq} hkv={hkv} d={d} scale={scale:.4f}", flush=True)
     cu, q, k, v, do = wl.custom(lengths, hq, hkv, d, "bf16", 70 + seed)
     got = gu.run_gpu(cu, q, k, v, do, "bf16", scale, host_cu=bool(seed & 1))
-    o, lse = orc.fwd(q, k, v, cu, scale)
-    dq, dk, dv = orc.bwd(q, k, v, do, cu, scale)
     failures = []
-    for name, ref in (("o", o), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
-        gu.check(name, got[name], ref, "bf16", failures=failures)
+    gu.check_all(got, q, k, v, do, cu, scale, "bf16", failures, orc)
     assert not failures, "\n".join(failures)
     # one range visit: queries from row 256 on against the keys before them
     if max(lengths) > 256:

@@ -235,7 +235,7 @@ def test_partial_gradients_of_a_ring_sum_to_the_plain_backward():
 def test_config2_ring_at_full_size():
     """Configuration 2 (the benchmark's headline buffer) under CP = 2, every visit of both ranks:
     the merged forward and the summed partial gradients against sampled oracle rows and keys."""
-    from paper_2412_07894_amd import cp_study
+    import cp_study
     cid, cp = 2, 2
     cfg = wl.CONFIGS[cid]
     lengths = [int(x) for x in wl.seqlens(cid)]

@@ -204,6 +204,44 @@ def test_linearity_in_v_and_do():
         assert np.allclose(b, -4.0 * a, rtol=1e-13, atol=1e-15)
 
 
+def test_backward_given_stored_forward_results():
+    """hyd_oracle_bwd_given (the backward as a function of the stored O and LSE it is handed)."""
+    cu, q, k, v, do, sc = case([5, 1, 12, 0, 33], 4, 2, 8, seed=23)
+    o, lse = orc.fwd(q, k, v, cu, sc)
+    dq, dk, dv = orc.bwd(q, k, v, do, cu, sc)
+    # (1) on the exact O and LSE it is the plain backward (float32 copies: 6e-8 relative)
+    for a, b in zip(orc.bwd_given(q, k, v, do, o, lse, cu, sc), (dq, dk, dv)):
+        assert np.max(np.abs(a - b)) <= 2e-6 * max(1.0, np.max(np.abs(b)))
+    # (2) perturbed O and LSE against the matrix form in numpy
+    rng = np.random.default_rng(3)
+    o_p = (o + 0.05 * rng.standard_normal(o.shape)).astype(np.float32)
+    lse_p = (lse + 0.1 * rng.standard_normal(lse.shape)).astype(np.float32)
+    got = orc.bwd_given(q, k, v, do, o_p, lse_p, cu, sc)
+    for a, b in zip(got, brute.packed_given(q, k, v, cu, sc, do, o_p, lse_p)):
+        assert np.max(np.abs(a - b)) <= 1e-12 * max(1.0, np.max(np.abs(b)))
+    # (3) closed forms.  LSE + c for all rows: every P, hence every gradient, times exp(-c)
+    c = 0.25
+    lse32 = lse.astype(np.float32)
+    base = orc.bwd_given(q, k, v, do, o_p, lse32, cu, sc)
+    shifted = orc.bwd_given(q, k, v, do, o_p, lse32 + np.float32(c), cu, sc)
+    for a, b in zip(shifted, base):
+        assert np.allclose(a, np.exp(-c) * b, rtol=1e-6, atol=1e-6)    # lse + c is rounded to float32 row by row
+    # O + delta in one row i of head h moves D_i by <dO_i, delta> and with it
+    # dQ_i by -scale <dO_i, delta> sum_j P_ij K_j = -scale <dO_i, delta> * (the attention output over K)
+    exact = orc.bwd_given(q, k, v, do, o.astype(np.float32), lse32, cu, sc)
+    i, h = int(cu[2]) + 7, 3
+    delta = rng.standard_normal(o.shape[2]).astype(np.float32)
+    o_d = o.astype(np.float32).copy()
+    o_d[i, h] += delta
+    moved = orc.bwd_given(q, k, v, do, o_d, lse32, cu, sc)
+    d_exact = float(np.dot(do[i, h].astype(np.float64), (o_d[i, h].astype(np.float64) - o.astype(np.float32)[i, h].astype(np.float64))))
+    ok_attn, _ = orc.fwd(q, k, k, cu, sc)                   # softmax(QK^T) K: V replaced by K
+    want = -sc * d_exact * ok_attn[i, h]
+    assert np.allclose(moved[0][i, h] - exact[0][i, h], want, rtol=1e-5, atol=1e-8)
+    other = np.ones(o.shape[0], dtype=bool); other[i] = False
+    assert np.array_equal(moved[0][other], exact[0][other]) and np.array_equal(moved[2], exact[2])   # dV does not depend on O
+
+
 def test_sampled_rows_and_cols_agree_with_full():
     """The one-output-at-a-time entry points are the same definition; they are pinned to the
     brute force directly."""
