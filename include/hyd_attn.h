@@ -68,9 +68,10 @@ const char* hyd_status_string(hyd_status st);
  * Bytes of device workspace that hyd_varlen_attn_fwd (is_bwd = 0) or hyd_varlen_attn_bwd
  * (is_bwd = 1) needs for these sizes.  The workspace holds the work-item schedule (the list of
  * (sequence, tile) items ordered by decreasing cost, and the queue cursors of the persistent
- * workgroups) and, for the backward, two float vectors [Hq][T]: D = rowsum(dO * O) and LSE in
- * base-2 units (the bf16 kernels keep both negated; their contents are private to the library).
- * Returns 0 for invalid arguments.  Pure host arithmetic: no HIP call.
+ * workgroups) and, for the backward, float vectors [Hq][T] of row statistics (D = rowsum(dO * O)
+ * and LSE in base-2 units, negated, in the forms the two kernels consume) plus, for bf16, fp16
+ * copies of Q, dO and K (2 * T * (2 Hq + Hkv) * head_dim bytes); the contents are private to the
+ * library.  Returns 0 for invalid arguments.  Pure host arithmetic: no HIP call.
  */
 size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, int hkv,
                                        int head_dim, hyd_dtype dt, int is_bwd);
@@ -110,9 +111,19 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v,
  *   d_o              device, [T][Hq][d], same dtype
  *   dq, dk, dv       device, outputs, fully overwritten (no atomics: bitwise reproducible)
  *   workspace        device, >= hyd_varlen_attn_workspace_bytes(..., 1) bytes, 256-byte aligned
- * Three kernels are enqueued after the schedule prelude (one launch for both item lists): D = rowsum(dO*O); dK/dV (one work item
- * per (sequence, key tile, KV head), looping over the group's query heads); dQ (one work item
- * per (sequence, query tile, query head)).
+ * Four kernels are enqueued after the schedule prelude (one launch for both item lists): row
+ * statistics (D = rowsum(dO * O), the largest |dO| of each row and of the tensor); fp16 copies of
+ * Q, K and dO; dK/dV (one work item per (sequence, key tile, KV head), looping over the group's
+ * query heads); dQ (one work item per (sequence, query tile, query head)).
+ *
+ * Arithmetic of the bf16 path: the tile products run on the fp16 matrix instructions with fp32
+ * accumulation, so that the factors formed in registers (P, dS) keep 11 significant bits.  bf16
+ * inputs convert to fp16 exactly for magnitudes in [2^-14, 65504]; Q, K or V values beyond 65504
+ * become infinite (the gradients are then non-finite), values below 2^-14 keep an absolute
+ * accuracy of 2^-25.  dO may have any scale: it is brought into range by powers of two (one per
+ * tensor for dK and dV, one per row for dQ) that are undone in the results.  D is formed from the
+ * o that is passed in: where o has been rounded to bf16, dQ and dK carry that rounding
+ * (<dO_i, delta O_i> enters every dS_ij of the row), whatever the arithmetic of the kernels.
  */
 hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o,
                                const float* lse, const void* d_o,
