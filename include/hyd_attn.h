@@ -135,6 +135,26 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward without a workspace argument, for callers that cannot allocate device memory or carry a
+ * workspace around (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation): same computation and results as hyd_varlen_attn_fwd, with the schedule kept in a
+ * fixed array inside the library (hyd_varlen_attn_fwd_noalloc_max_workspace() bytes per GPU,
+ * held until the process ends).  It calls no hipMalloc / hipFree and no allocating routine.
+ * Sizes whose forward workspace (hyd_varlen_attn_workspace_bytes(..., 0)) exceeds that array
+ * are rejected with HYD_ERR_WORKSPACE before any HIP call; 2 MiB cover, for example, one million
+ * tokens in 65536 sequences.  All calls on one GPU share the one array: two calls whose kernels
+ * overlap in time (different streams, or different host threads) race on it, so serialise them.
+ * Argument checks, errors and stream semantics otherwise as hyd_varlen_attn_fwd.
+ */
+hyd_status hyd_varlen_attn_fwd_noalloc(const void* q, const void* k, const void* v,
+                                       const int32_t* cu_seqlens, int num_seqs,
+                                       const int32_t* cu_seqlens_host,
+                                       int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                                       float softmax_scale, hyd_dtype dt,
+                                       void* o, float* lse, void* hip_stream);
+size_t hyd_varlen_attn_fwd_noalloc_max_workspace(void);
+
+/*
  * Range variants: the building block of context parallelism (CP, one axis of the paper's
  * <TP, PP, CP> schemes, Sec. 2.1 and App. C.1).  Under CP a device holds one chunk of every
  * sequence's queries while the key/value chunks visit it one after the other; each visit

@@ -16,6 +16,7 @@ EXPORTS = (
     "hyd_status_string", "hyd_varlen_attn_workspace_bytes", "hyd_varlen_attn_fwd",
     "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
     "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
+    "hyd_varlen_attn_fwd_noalloc", "hyd_varlen_attn_fwd_noalloc_max_workspace",
 )
 RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
@@ -43,6 +44,10 @@ def load():
     lib.hyd_varlen_attn_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.hyd_varlen_attn_fwd.restype = i
     lib.hyd_varlen_attn_fwd.argtypes = [vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i, vp, vp, vp, sz, vp]
+    lib.hyd_varlen_attn_fwd_noalloc.restype = i
+    lib.hyd_varlen_attn_fwd_noalloc.argtypes = [vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i, vp, vp, vp]
+    lib.hyd_varlen_attn_fwd_noalloc_max_workspace.restype = sz
+    lib.hyd_varlen_attn_fwd_noalloc_max_workspace.argtypes = []
     lib.hyd_varlen_attn_bwd.restype = i
     lib.hyd_varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i,
                                         vp, vp, vp, vp, sz, vp]
@@ -124,6 +129,22 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_h
                                    o.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
                                    _stream_ptr(stream)))
     return o, lse
+
+
+def varlen_attn_fwd_noalloc(q, k, v, cu_seqlens, max_seqlen, softmax_scale, out, lse, cu_seqlens_host=None, stream=None):
+    """The forward without a workspace: the library keeps the schedule in an array of its own
+    (see the header); `out` and `lse` are caller-owned, nothing is allocated here or there."""
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    for t in (q, k, v, out, lse, cu_seqlens):
+        assert t.is_contiguous()
+    assert out.shape == q.shape and out.dtype == q.dtype and lse.dtype == torch.float32 and lse.shape == (hq, T)
+    keep, hp = _host_ptr(cu_seqlens_host)
+    _check(load().hyd_varlen_attn_fwd_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(),
+                                              cu_seqlens.numel() - 1, hp, T, int(max_seqlen), hq, hkv, d,
+                                              float(softmax_scale), _dtype_code(q), out.data_ptr(), lse.data_ptr(),
+                                              _stream_ptr(stream)))
+    return out, lse
 
 
 def varlen_attn_bwd(q, k, v, o, lse, d_o, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_host=None,

@@ -144,11 +144,20 @@ hyd_status validate_ranges(const int32_t* ranges, const int32_t* ranges_host, co
     return HYD_OK;
 }
 
+// ---- library-owned scratch of the entry point that allocates nothing ---------------------------
+// Holds the forward's workspace (one schedule) for callers that cannot provide one.  Every GPU the
+// library runs on keeps its own copy of this array until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address kernels and memory calls use
+// is DeviceInfo::scratch, looked up once per device.
+constexpr size_t kScratchBytes = 2u << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 // ---- per-device state -------------------------------------------------------------------------
 struct DeviceInfo {
     bool ready = false, ok = false;
     int cus = 0;
     int occ_fwd = 1, occ_dq = 1, occ_kv = 1;
+    void* scratch = nullptr;          // this device's copy of the array above
 };
 DeviceInfo g_dev[64];
 std::mutex g_dev_mutex;       // first use of a device from several host threads at once
@@ -190,6 +199,9 @@ hyd_status device_info(DeviceInfo** out) {
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<64>, kF32Tile, f32_dkdv_lds<64>(), nullptr) ||
                 !prep_kernel(hyd_bwd_dkdv_fp32_kernel<128>, kF32Tile, f32_dkdv_lds<128>(), nullptr))
                 return HYD_ERR_LAUNCH;
+            void* sp = nullptr;
+            if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) return HYD_ERR_LAUNCH;
+            d.scratch = sp;
         }
         d.ready = true;
     }
@@ -481,6 +493,32 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
     return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false, total_tokens,
                     max_seqlen, hq, hkv, head_dim, softmax_scale, dt, o, lse, workspace, workspace_bytes,
                     hip_stream);
+}
+
+size_t hyd_varlen_attn_fwd_noalloc_max_workspace(void) { return kScratchBytes; }
+
+hyd_status hyd_varlen_attn_fwd_noalloc(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                                       int num_seqs, const int32_t* cu_seqlens_host, int total_tokens,
+                                       int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
+                                       hyd_dtype dt, void* o, float* lse, void* hip_stream) {
+    // sizes first (no HIP call yet): the forward's workspace for these sizes must fit the array
+    if (total_tokens < 0 || num_seqs < 0) return HYD_ERR_SHAPE;
+    if (hq <= 0 || hkv <= 0 || hq % hkv != 0) return HYD_ERR_HEADS;
+    if (dt != HYD_BF16 && dt != HYD_FP32) return HYD_ERR_DTYPE;
+    if (!head_dim_ok(dt, head_dim)) return HYD_ERR_HEADDIM;
+    if (hyd_varlen_attn_workspace_bytes(total_tokens, num_seqs, hq, hkv, head_dim, dt, 0) > kScratchBytes)
+        return HYD_ERR_WORKSPACE;
+    // the rest of the argument checks, still before any HIP call (a stand-in for the workspace pointer)
+    const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen, hq, hkv, head_dim,
+                                          dt, reinterpret_cast<const void*>(kAlign), kScratchBytes, false);
+    if (vs != HYD_OK) return vs;
+    if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
+    if (!q || !k || !v || !o || !lse) return HYD_ERR_NULL;
+    DeviceInfo* dev = nullptr;
+    const hyd_status ds = device_info(&dev);          // first call on a device: looks the array's address up
+    if (ds != HYD_OK) return ds;
+    return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false, total_tokens, max_seqlen,
+                    hq, hkv, head_dim, softmax_scale, dt, o, lse, dev->scratch, kScratchBytes, hip_stream);
 }
 
 hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,

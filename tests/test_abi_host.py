@@ -169,3 +169,22 @@ def test_status_strings(lib):
     seen = {b.status_string(c) for c in range(12)}
     assert len(seen) == 12 and all(s.startswith("HYD_") for s in seen)
     assert "unknown" in b.status_string(99)
+
+
+def test_noalloc_forward_checks_sizes_and_arguments_before_any_hip_call(lib):
+    """hyd_varlen_attn_fwd_noalloc on a host without a GPU: every argument error is reported, and
+    sizes beyond the library's fixed array are HYD_ERR_WORKSPACE."""
+    P = ctypes.c_void_p(1 << 20)
+    f = ctypes.c_float(0.1)
+    lib.hyd_varlen_attn_fwd_noalloc.restype = ctypes.c_int
+    lib.hyd_varlen_attn_fwd_noalloc_max_workspace.restype = ctypes.c_size_t
+    call = lambda **kw: lib.hyd_varlen_attn_fwd_noalloc(*[{**dict(q=P, k=P, v=P, cu=P, nseq=3, cuh=None, T=1000, ml=500, hq=8, hkv=2,
+                                                                 d=128, sc=f, dt=0, o=P, lse=P, st=None), **kw}[k]
+                                                         for k in ("q", "k", "v", "cu", "nseq", "cuh", "T", "ml", "hq", "hkv", "d", "sc", "dt", "o", "lse", "st")])
+    assert lib.hyd_varlen_attn_fwd_noalloc_max_workspace() == 2 << 20
+    assert call(T=-1) == 2 and call(hq=7) == 4 and call(dt=5) == 3 and call(d=96) == 5
+    assert call(cu=None) == 1 and call(q=None) == 1 and call(o=None) == 1 and call(ml=2000) == 2
+    bad = (ctypes.c_int32 * 4)(0, 10, 5, 1000)
+    assert call(cuh=ctypes.cast(bad, ctypes.c_void_p)) == 6
+    assert call(T=1 << 24, nseq=1 << 20, ml=4096) == 7          # schedule larger than the array
+    assert call(T=0, nseq=0, q=None, k=None, v=None, cu=None, o=None, lse=None) == 0
