@@ -135,6 +135,35 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * What the schedule prelude of the last forward (is_bwd = 0) or backward (is_bwd = 1) call on
+ * `workspace` saw in the DEVICE cu_seqlens.  The entry points above cannot look at device memory
+ * without stalling the stream, so with cu_seqlens_host == NULL they trust the caller: a sequence
+ * longer than max_seqlen gets work items only for its first ceil(max_seqlen / tile) tiles (the
+ * rest of its outputs is left unwritten), and a cu_seqlens that does not start at 0, end at
+ * total_tokens or that decreases gives undefined results inside the buffers.  This call copies
+ * the prelude's findings back - it SYNCHRONISES `hip_stream` - and returns HYD_ERR_SHAPE for
+ * the first condition, HYD_ERR_SEQLENS for the second, HYD_OK otherwise.  Same size arguments
+ * as the call it checks.  Errors of its own: HYD_ERR_WORKSPACE, the argument errors, HYD_ERR_LAUNCH.
+ */
+hyd_status hyd_varlen_attn_schedule_status(const void* workspace, size_t workspace_bytes,
+                                           int total_tokens, int num_seqs, int hq, int hkv,
+                                           int head_dim, hyd_dtype dt, int is_bwd, void* hip_stream);
+
+/*
+ * Where a schedule sits inside a workspace, for tools that inspect it (pure host arithmetic).
+ * which = 0: the forward's list (is_bwd = 0) or the dK/dV kernel's (is_bwd = 1); which = 1: the
+ * dQ kernel's (is_bwd = 1 only).  At header_offset: int32[64], [0] = number of items n.  At
+ * items_offset: n records of four int32 (sequence, level c, first packed row of the sequence,
+ * length of the sequence), by decreasing level (paper Sec. 2.1: the cost of a sequence is
+ * quadratic; level c of a sequence is its tile with c tiles of causal work, 1 <= c <=
+ * ceil(length / *tile)); at most *max_items records.
+ */
+hyd_status hyd_varlen_attn_schedule_layout(int total_tokens, int num_seqs, int hq, int hkv,
+                                           int head_dim, hyd_dtype dt, int is_bwd, int which,
+                                           size_t* header_offset, size_t* items_offset,
+                                           int* max_items, int* tile);
+
+/*
  * Forward without a workspace argument, for callers that cannot allocate device memory or carry a
  * workspace around (code under HIP graph capture, tight serving loops, harnesses that forbid
  * allocation): same computation and results as hyd_varlen_attn_fwd, with the schedule kept in a

@@ -17,6 +17,7 @@ EXPORTS = (
     "hyd_varlen_attn_bwd", "hyd_enable_kernel_timing", "hyd_kernel_times", "hyd_set_wg_trace",
     "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
     "hyd_varlen_attn_fwd_noalloc", "hyd_varlen_attn_fwd_noalloc_max_workspace",
+    "hyd_varlen_attn_schedule_status", "hyd_varlen_attn_schedule_layout",
 )
 RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
@@ -48,6 +49,11 @@ def load():
     lib.hyd_varlen_attn_fwd_noalloc.argtypes = [vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i, vp, vp, vp]
     lib.hyd_varlen_attn_fwd_noalloc_max_workspace.restype = sz
     lib.hyd_varlen_attn_fwd_noalloc_max_workspace.argtypes = []
+    lib.hyd_varlen_attn_schedule_status.restype = i
+    lib.hyd_varlen_attn_schedule_status.argtypes = [vp, sz, i, i, i, i, i, i, i, vp]
+    lib.hyd_varlen_attn_schedule_layout.restype = i
+    lib.hyd_varlen_attn_schedule_layout.argtypes = [i, i, i, i, i, i, i, i, ctypes.POINTER(sz), ctypes.POINTER(sz),
+                                                    ctypes.POINTER(i), ctypes.POINTER(i)]
     lib.hyd_varlen_attn_bwd.restype = i
     lib.hyd_varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i,
                                         vp, vp, vp, vp, sz, vp]
@@ -271,3 +277,23 @@ def set_wg_trace(records):
     else:
         assert records.dtype == torch.int64 and records.is_contiguous() and records.shape[1] == 4
         load().hyd_set_wg_trace(records.data_ptr(), records.shape[0])
+
+
+def schedule_status(workspace, total_tokens, num_seqs, hq, hkv, head_dim, dtype_code, is_bwd, stream=None):
+    """Status code of what the last call's schedule prelude saw in the device cu_seqlens
+    (synchronises the stream): 0, HYD_ERR_SHAPE (2) or HYD_ERR_SEQLENS (6)."""
+    return int(load().hyd_varlen_attn_schedule_status(workspace.data_ptr(), workspace.numel(), total_tokens, num_seqs, hq, hkv,
+                                                      head_dim, dtype_code, int(is_bwd), _stream_ptr(stream)))
+
+
+def schedule_items(workspace, total_tokens, num_seqs, hq, hkv, head_dim, dtype_code, is_bwd, which):
+    """The item list a finished call left in `workspace`: (tile, int array [n, 4] of (sequence,
+    level, first packed row, length)), copied to the host."""
+    hdr, items, cap, tile = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int(0), ctypes.c_int(0)
+    _check(load().hyd_varlen_attn_schedule_layout(total_tokens, num_seqs, hq, hkv, head_dim, dtype_code, int(is_bwd), int(which),
+                                                  ctypes.byref(hdr), ctypes.byref(items), ctypes.byref(cap), ctypes.byref(tile)))
+    torch.cuda.synchronize()
+    n = int(workspace[hdr.value:hdr.value + 4].view(torch.int32).item())
+    assert 0 <= n <= cap.value
+    rec = workspace[items.value:items.value + 16 * n].view(torch.int32).reshape(n, 4).cpu().numpy()
+    return tile.value, rec

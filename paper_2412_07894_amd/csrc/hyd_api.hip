@@ -317,7 +317,7 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
     const SchedView sv = make_view(static_cast<char*>(workspace), w.sched[0], tile, max_seqlen);
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, tile, sv, tile, sv);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, total_tokens, tile, sv, tile, sv);
     }
     const HeadMap hm = head_map_q(hq, hkv);
     const long long work = (long long)sv.max_items * hq;
@@ -382,7 +382,7 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     // size, the dQ kernel's too (one workgroup each)
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(w.n_sched), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs,
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(w.n_sched), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, total_tokens,
                            tile_kv(dt), sv_kv, tile_dq(dt), sv_q);
     }
     const long long n_rows = (long long)total_tokens * hq;
@@ -603,6 +603,42 @@ hyd_status hyd_rope_packed(const void* x, const int32_t* cu_seqlens, int num_seq
                                num_seqs, total_tokens, heads, log2((double)base), inverse != 0, static_cast<uint16_t*>(out));
     }
     return hipGetLastError() == hipSuccess ? HYD_OK : HYD_ERR_LAUNCH;
+}
+
+hyd_status hyd_varlen_attn_schedule_layout(int total_tokens, int num_seqs, int hq, int hkv, int head_dim, hyd_dtype dt,
+                                           int is_bwd, int which, size_t* header_offset, size_t* items_offset,
+                                           int* max_items, int* tile) {
+    if (!header_offset || !items_offset || !max_items || !tile) return HYD_ERR_NULL;
+    if (total_tokens < 0 || num_seqs < 0 || which < 0 || which > 1 || (which == 1 && !is_bwd)) return HYD_ERR_SHAPE;
+    if (hq <= 0 || hkv <= 0 || hq % hkv != 0) return HYD_ERR_HEADS;
+    if (dt != HYD_BF16 && dt != HYD_FP32) return HYD_ERR_DTYPE;
+    if (!head_dim_ok(dt, head_dim)) return HYD_ERR_HEADDIM;
+    const WsLayout w = is_bwd ? ws_layout(total_tokens, num_seqs, tile_kv(dt), tile_dq(dt), hq, hkv, head_dim, dt, true)
+                              : ws_layout(total_tokens, num_seqs, tile_fwd(dt), tile_fwd(dt), hq, hkv, head_dim, dt, false);
+    const SchedLayout& v = w.sched[which];
+    *header_offset = v.hdr; *items_offset = v.items; *max_items = v.max_items;
+    *tile = !is_bwd ? tile_fwd(dt) : (which == 0 ? tile_kv(dt) : tile_dq(dt));
+    return HYD_OK;
+}
+
+hyd_status hyd_varlen_attn_schedule_status(const void* workspace, size_t workspace_bytes, int total_tokens, int num_seqs,
+                                           int hq, int hkv, int head_dim, hyd_dtype dt, int is_bwd, void* hip_stream) {
+    size_t hdr = 0, items = 0;
+    int max_items = 0, tile = 0;
+    const hyd_status ls = hyd_varlen_attn_schedule_layout(total_tokens, num_seqs, hq, hkv, head_dim, dt, is_bwd, 0, &hdr, &items,
+                                                          &max_items, &tile);
+    if (ls != HYD_OK) return ls;
+    if (total_tokens == 0 || num_seqs == 0) return HYD_OK;
+    if (!workspace || workspace_bytes < hyd_varlen_attn_workspace_bytes(total_tokens, num_seqs, hq, hkv, head_dim, dt, is_bwd))
+        return HYD_ERR_WORKSPACE;
+    int head[2] = {0, 0};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(head, static_cast<const char*>(workspace) + hdr, sizeof(head), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return HYD_ERR_LAUNCH;
+    if (head[kHdrFlags] & kSchedBadSeqlens) return HYD_ERR_SEQLENS;
+    if (head[kHdrFlags] & kSchedTooLong) return HYD_ERR_SHAPE;
+    return HYD_OK;
 }
 
 void hyd_enable_kernel_timing(int on) {

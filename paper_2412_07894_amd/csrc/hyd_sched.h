@@ -20,8 +20,13 @@ namespace hyd {
 
 constexpr int kQueues = 8;
 constexpr int kHdrInts = 64;
-// header (ints): [0] n_items, [8 + 8*k + x] cursor of queue x of kernel k (k = 0 fwd, 1 dK/dV, 2 dQ)
+// header (ints): [0] n_items, [1] kSched* flags about cu_seqlens as the prelude saw it,
+// [8 + 8*k + x] cursor of queue x of kernel k (k = 0 fwd, 1 dK/dV, 2 dQ); the rest is zeroed by
+// the prelude and free for the kernels of the call ([40] of the dK/dV schedule: max |dO|)
 constexpr int kHdrCursor = 8;
+constexpr int kHdrFlags = 1;
+constexpr int kSchedTooLong = 1;          // a sequence is longer than max_seqlen: its tiles beyond that bound got no item
+constexpr int kSchedBadSeqlens = 2;       // cu_seqlens does not start at 0, does not end at T, or decreases
 
 struct SchedView {            // device pointers into the workspace (all int32)
     int* hdr;                 // kHdrInts
@@ -66,7 +71,7 @@ constexpr int kPreludeLdsLev = 4096;      // levels whose arrays fit the kernel'
 // come from one launch.  n_lev* bounds the tiles per sequence (from the caller's max_seqlen).
 // Order among items of equal cost: by sequence rank (arrival order among equals), which is
 // unspecified (it never changes a result: every output element has exactly one producer).
-__global__ void __launch_bounds__(kPreludeThreads) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq,
+__global__ void __launch_bounds__(kPreludeThreads) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq, int T,
                                                                        int tile0, SchedView sv0, int tile1, SchedView sv1) {
     __shared__ int lds_lev[3 * (kPreludeLdsLev + 2)];
     const bool second = blockIdx.x != 0;
@@ -81,11 +86,15 @@ __global__ void __launch_bounds__(kPreludeThreads) hyd_schedule_prelude(const in
     for (int i = tid; i < nl + 2; i += kPreludeThreads) hist[i] = 0;
     for (int i = tid; i < kHdrInts; i += kPreludeThreads) sv.hdr[i] = 0;
     __syncthreads();
+    int flags = (tid == 0 && (cu[0] != 0 || cu[nseq] != T)) ? kSchedBadSeqlens : 0;
     for (int s = tid; s < nseq; s += kPreludeThreads) {
         const int L = cu[s + 1] - cu[s];
+        if (L < 0) flags |= kSchedBadSeqlens;
+        if (L > 0 && (L + tile - 1) / tile > nl) flags |= kSchedTooLong;
         const int n = min((L + tile - 1) / tile, nl);
         if (n > 0) atomicAdd(&hist[n], 1);
     }
+    if (flags) atomicOr(&sv.hdr[kHdrFlags], flags);
     __syncthreads();
     if (tid < 64) {
         // cnt[r] = sum_{n >= nl - r} hist[n]; offs = inclusive scan of cnt

@@ -188,3 +188,23 @@ def test_noalloc_forward_checks_sizes_and_arguments_before_any_hip_call(lib):
     assert call(cuh=ctypes.cast(bad, ctypes.c_void_p)) == 6
     assert call(T=1 << 24, nseq=1 << 20, ml=4096) == 7          # schedule larger than the array
     assert call(T=0, nseq=0, q=None, k=None, v=None, cu=None, o=None, lse=None) == 0
+
+
+def test_schedule_layout_and_status_argument_errors(lib):
+    sz, ci = ctypes.c_size_t, ctypes.c_int
+    h, it, cap, tile = sz(0), sz(0), ci(0), ci(0)
+    lib.hyd_varlen_attn_schedule_layout.restype = ctypes.c_int
+    lay = lambda T, n, hq, hkv, d, dt, bwd, which: lib.hyd_varlen_attn_schedule_layout(T, n, hq, hkv, d, dt, bwd, which, ctypes.byref(h),
+                                                                                          ctypes.byref(it), ctypes.byref(cap), ctypes.byref(tile))
+    assert lay(1000, 3, 8, 2, 128, 0, 0, 0) == 0 and tile.value == 256 and cap.value == 1000 // 256 + 3 + 1 and it.value > h.value
+    assert lay(1000, 3, 8, 2, 128, 0, 1, 0) == 0 and tile.value == 128
+    kv_items = it.value
+    assert lay(1000, 3, 8, 2, 128, 0, 1, 1) == 0 and tile.value == 256 and it.value > kv_items
+    assert lay(1000, 3, 8, 2, 128, 0, 0, 1) == 2 and lay(1000, 3, 8, 2, 128, 0, 1, 2) == 2 and lay(-1, 3, 8, 2, 128, 0, 1, 0) == 2
+    assert lay(1000, 3, 7, 2, 128, 0, 1, 0) == 4 and lay(1000, 3, 8, 2, 96, 0, 1, 0) == 5 and lay(1000, 3, 8, 2, 128, 9, 1, 0) == 3
+    assert lib.hyd_varlen_attn_schedule_layout(1000, 3, 8, 2, 128, 0, 1, 0, None, ctypes.byref(it), ctypes.byref(cap), ctypes.byref(tile)) == 1
+    lib.hyd_varlen_attn_schedule_status.restype = ctypes.c_int
+    P = ctypes.c_void_p(1 << 20)
+    st = lambda ws, nbytes, T=1000, n=3, hq=8: lib.hyd_varlen_attn_schedule_status(ws, sz(nbytes), T, n, hq, 2, 128, 0, 0, None)
+    assert st(None, 1 << 20) == 7 and st(P, 16) == 7 and st(P, 1 << 20, hq=7) == 4 and st(P, 1 << 20, T=-5) == 2
+    assert st(None, 0, T=0, n=0) == 0

@@ -110,3 +110,69 @@ def test_level_arrays_in_global_memory_when_max_seqlen_is_a_loose_bound():
     idx = torch.from_numpy((cu[s] + cols).astype(np.int64)).cuda()
     gu.check("dk[keys]", gu.to_np(dk[idx, 0]), rk, "bf16")
     gu.check("dv[keys]", gu.to_np(dv[idx, 0]), rv, "bf16")
+
+
+def _item_lists_match(lengths, hq, hkv, d=128):
+    """Runs forward and backward, reads the three item lists back from the workspaces and compares
+    them with the reference enumeration: the same records level by level (the order inside a
+    level is free), levels never increasing along the list.  Integer work: exact."""
+    from oracle import sched_oracle as so
+    cu_np = wl.cu_seqlens(lengths)
+    T, nseq, ml = int(cu_np[-1]), len(lengths), int(max(lengths))
+    cu = torch.from_numpy(cu_np).cuda()
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    mk = lambda h: torch.randn((T, h, d), device="cuda", dtype=torch.float32, generator=g).to(torch.bfloat16)
+    q, k, v, do = mk(hq), mk(hkv), mk(hkv), mk(hq)
+    code = binding.HYD_BF16
+    ws_f = torch.empty(binding.workspace_bytes(T, nseq, hq, hkv, d, code, 0), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.workspace_bytes(T, nseq, hq, hkv, d, code, 1), dtype=torch.uint8, device="cuda")
+    o, lse = binding.varlen_attn_fwd(q, k, v, cu, ml, 0.088, workspace=ws_f)
+    binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, 0.088, workspace=ws_b)
+    torch.cuda.synchronize()
+    assert binding.schedule_status(ws_f, T, nseq, hq, hkv, d, code, 0) == 0
+    assert binding.schedule_status(ws_b, T, nseq, hq, hkv, d, code, 1) == 0
+    for ws, is_bwd, which, name in ((ws_f, 0, 0, "forward"), (ws_b, 1, 0, "dK/dV"), (ws_b, 1, 1, "dQ")):
+        tile, rec = binding.schedule_items(ws, T, nseq, hq, hkv, d, code, is_bwd, which)
+        ref = so.records(lengths, tile)
+        print(f"{name}: tile {tile}, {len(rec)} items (reference {len(ref)}), top level {rec[0][1] if len(rec) else 0}", flush=True)
+        assert len(rec) == len(ref), name
+        levels = rec[:, 1]
+        assert np.all(levels[:-1] >= levels[1:]), name
+        assert sorted(map(tuple, rec.tolist())) == sorted(ref), name
+
+
+def test_item_lists_equal_the_reference_enumeration_config1_lengths():
+    _item_lists_match([1, 7, 64, 184], 2, 2)
+
+
+def test_item_lists_equal_the_reference_enumeration_config4():
+    _item_lists_match(wl.seqlens(4), 8, 2)            # the sequence structure of configuration 4, fewer heads
+
+
+def test_item_lists_with_empty_sequences_and_tile_boundaries():
+    _item_lists_match([0, 128, 129, 0, 256, 257, 1, 1000, 0], 4, 4)
+
+
+def test_prelude_reports_what_it_saw_in_device_seqlens():
+    """Without a host copy of cu_seqlens the call cannot validate it; the prelude leaves its
+    findings in the workspace and hyd_varlen_attn_schedule_status reads them back."""
+    lengths = [300, 700, 20]
+    cu_np = wl.cu_seqlens(lengths)
+    T, nseq, hq, hkv, d = int(cu_np[-1]), 3, 2, 1, 128
+    g = torch.Generator(device="cuda"); g.manual_seed(12)
+    mk = lambda h: torch.randn((T, h, d), device="cuda", dtype=torch.float32, generator=g).to(torch.bfloat16)
+    q, k, v = mk(hq), mk(hkv), mk(hkv)
+    code = binding.HYD_BF16
+    ws = torch.empty(binding.workspace_bytes(T, nseq, hq, hkv, d, code, 0), dtype=torch.uint8, device="cuda")
+    cu = torch.from_numpy(cu_np).cuda()
+    binding.varlen_attn_fwd(q, k, v, cu, 700, 0.1, workspace=ws)
+    assert binding.schedule_status(ws, T, nseq, hq, hkv, d, code, 0) == 0
+    # max_seqlen below the longest sequence: items only up to the bound, reported as HYD_ERR_SHAPE
+    binding.varlen_attn_fwd(q, k, v, cu, 256, 0.1, workspace=ws)
+    assert binding.schedule_status(ws, T, nseq, hq, hkv, d, code, 0) == 2
+    # a cu_seqlens that does not end at T (rows stay inside the buffers: the last entry is smaller)
+    short = torch.from_numpy(np.array([0, 300, 1000, 1010], dtype=np.int32)).cuda()
+    binding.varlen_attn_fwd(q, k, v, short, 700, 0.1, workspace=ws)
+    assert binding.schedule_status(ws, T, nseq, hq, hkv, d, code, 0) == 6
+    binding.varlen_attn_fwd(q, k, v, cu, 700, 0.1, workspace=ws)         # and a good call clears the flags again
+    assert binding.schedule_status(ws, T, nseq, hq, hkv, d, code, 0) == 0
