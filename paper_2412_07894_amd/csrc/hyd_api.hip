@@ -398,44 +398,25 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
         sc.q16 = reinterpret_cast<uint16_t*>(ws + w.q16);
         sc.do16 = reinterpret_cast<uint16_t*>(ws + w.do16);
         sc.k16 = reinterpret_cast<uint16_t*>(ws + w.k16);
-        const dim3 rgrid((unsigned)((n_rows + 15) / 16));
         {
             KernelTimer kt("bwd_rowstats_bf16", st);
+            const dim3 rgrid((unsigned)((total_tokens + kStatTok - 1) / kStatTok));
             if (head_dim == 64)
-                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, sc, total_tokens, hq);
+                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<64>, rgrid, dim3(256), rowstats_lds(hq), st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
             else
-                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, sc, total_tokens, hq);
-        }
-        {
-            KernelTimer kt("bwd_convert_bf16", st);
-            if (head_dim == 64)
-                hipLaunchKernelGGL(hyd_bwd_convert_bf16_kernel<64>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                                   static_cast<const uint16_t*>(d_o), static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
-            else
-                hipLaunchKernelGGL(hyd_bwd_convert_bf16_kernel<kHeadDim>, rgrid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                                   static_cast<const uint16_t*>(d_o), static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
+                hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<kHeadDim>, rgrid, dim3(256), rowstats_lds(hq), st, static_cast<const uint16_t*>(o),
+                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
         }
         BwdParams p;
-        p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
+        p.q = static_cast<const uint16_t*>(q); p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);
         p.sc = sc;
         p.dq = static_cast<uint16_t*>(dq); p.dk = static_cast<uint16_t*>(dk); p.dv = static_cast<uint16_t*>(dv);
         p.T = total_tokens; p.hq = hq; p.hkv = hkv;
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
         p.tr = t_trace;
         p.ranges = ranged ? ranges : nullptr;
-        {
-            p.hdr = sv_kv.hdr; p.items = sv_kv.items;
-            p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
-            const dim3 grid(persistent_grid(*dev, dev->occ_kv, work_kv));
-            KernelTimer kt(ranged ? "bwd_dkdv_range_bf16" : "bwd_dkdv_bf16", st);
-            if (head_dim == 64) {
-                if (ranged) hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<true, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
-                else hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<false, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
-            } else if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
-            else hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<false>, grid, dim3(kKvThreads), kKvLds, st, p);
-        }
+        // dQ first: it also writes the fp16 copies of Q and dO that dK/dV streams
         {
             p.hdr = sv_q.hdr; p.items = sv_q.items;
             p.cursors = sv_q.hdr + kHdrCursor + 2 * kQueues; p.hm = head_map_q(hq, hkv);
@@ -446,6 +427,17 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
                 else hipLaunchKernelGGL((hyd_bwd_dq_bf16_kernel<false, 64>), grid, dim3(kDqThreads), kDqLds, st, p);
             } else if (ranged) hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<true>, grid, dim3(kDqThreads), kDqLds, st, p);
             else hipLaunchKernelGGL(hyd_bwd_dq_bf16_kernel<false>, grid, dim3(kDqThreads), kDqLds, st, p);
+        }
+        {
+            p.hdr = sv_kv.hdr; p.items = sv_kv.items;
+            p.cursors = sv_kv.hdr + kHdrCursor + kQueues; p.hm = head_map_kv(hkv);
+            const dim3 grid(persistent_grid(*dev, dev->occ_kv, work_kv));
+            KernelTimer kt(ranged ? "bwd_dkdv_range_bf16" : "bwd_dkdv_bf16", st);
+            if (head_dim == 64) {
+                if (ranged) hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<true, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
+                else hipLaunchKernelGGL((hyd_bwd_dkdv_bf16_kernel<false, 64>), grid, dim3(kKvThreads), kKvLds, st, p);
+            } else if (ranged) hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<true>, grid, dim3(kKvThreads), kKvLds, st, p);
+            else hipLaunchKernelGGL(hyd_bwd_dkdv_bf16_kernel<false>, grid, dim3(kKvThreads), kKvLds, st, p);
         }
     } else {
         F32Params p;

@@ -44,83 +44,66 @@ struct BwdScratch {
     float* lse2q;       // [Hq][T]  -LSE * log2(e) + kq, kq = shift_of(row max |dO|) (dQ kernel: P * 2^kq)
     float* kqmul;       // [Hq][T]  2^-kq                                            (dQ kernel's epilogue)
     float* lse2kv;      // [Hq][T]  -LSE * log2(e)                                   (dK/dV kernel)
-    float* Dkv;         // [Hq][T]  -D * 2^kg, kg = shift_of(max |dO| of the tensor) (dK/dV kernel)
+    float* Dkv;         // [Hq][T]  -D * 2^kg, kg = shift_of(max |dO| of the tensor) (dK/dV kernel; written by dQ)
     uint32_t* absmax;   // max over dO of the 15-bit magnitude pattern; zeroed by the schedule prelude
-    uint16_t* q16;      // [T][Hq][d]  fp16 copy of Q
-    uint16_t* do16;     // [T][Hq][d]  fp16 copy of dO * 2^kg
-    uint16_t* k16;      // [T][Hkv][d] fp16 copy of K
+    uint16_t* q16;      // [T][Hq][d]  fp16 copy of Q          (written by the dQ kernel, read by dK/dV)
+    uint16_t* do16;     // [T][Hq][d]  fp16 copy of dO * 2^kg  (written by the dQ kernel, read by dK/dV)
+    uint16_t* k16;      // [T][Hkv][d] fp16 copy of K          (written by the statistics pass)
 };
 
 // ---------------------------------------------------------------------------------------------
-// Pass 1 over O and dO (16 lanes per row): the row statistics above except Dkv, and the tensor's
-// largest |dO|.  The statistics are stored NEGATED: the form in which the two backward kernels
-// consume them (P = exp2(s * scale * log2(e) + (-LSE2)), dS = P * (dP + (-D))), so that dK/dV can
-// use -D as the initial value of its dP accumulator.
+// One pass over O, dO and K before the tile kernels (16 lanes per row, 32 tokens per workgroup):
+// the row statistics above except Dkv, the tensor's largest |dO|, and the fp16 copy of K.  A
+// workgroup walks the rows of its tokens in memory order and collects their statistics in LDS, so
+// that the [Hq][T] vectors are written in runs of 32 consecutive floats.  The statistics are
+// stored NEGATED: the form in which the two backward kernels consume them
+// (P = exp2(s * scale * log2(e) + (-LSE2)), dS = P * (dP + (-D))), so that dK/dV can use -D as the
+// initial value of its dP accumulator.  (The fp16 copies of Q and dO and Dkv are written by the dQ
+// kernel, which has those rows in LDS anyway.)
 // ---------------------------------------------------------------------------------------------
+constexpr int kStatTok = 32;
+inline size_t rowstats_lds(int hq) { return sizeof(float) * 2 * (size_t)hq * kStatTok; }
+
 template <int HD = kHeadDim>
 __global__ void __launch_bounds__(256) hyd_bwd_rowstats_bf16_kernel(const uint16_t* __restrict__ o,
                                                                    const uint16_t* __restrict__ d_o,
                                                                    const float* __restrict__ lse,
-                                                                   BwdScratch sc, int T, int hq) {
-    const int64_t n_rows = (int64_t)T * hq;
-    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int c = threadIdx.x & 15;
-    float acc = 0.f;
-    uint32_t amax = 0;
-    if (row < n_rows && (HD == kHeadDim || c < HD / 8)) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + c * 8);
-        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + row * HD + c * 8);
+                                                                   const uint16_t* __restrict__ k,
+                                                                   BwdScratch sc, int T, int hq, int hkv) {
+    extern __shared__ float st[];                  // [2][hq][kStatTok]: -D, kq
+    const int t0 = blockIdx.x * kStatTok;
+    const int nt = min(kStatTok, T - t0);
+    const int grp = threadIdx.x >> 4, c = threadIdx.x & 15;
+    const bool lane_on = HD == kHeadDim || c < HD / 8;
+    uint32_t gmax = 0;
+    for (int r = grp; r < nt * hq; r += 16) {      // row r of the block = (token t0 + r / hq, head r % hq)
+        const int64_t at = ((int64_t)t0 * hq + r) * HD + c * 8;
+        float acc = 0.f;
+        uint32_t amax = 0;
+        if (lane_on) {
+            const u32x4 a = *reinterpret_cast<const u32x4*>(o + at);
+            const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + at);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
-            amax = max(amax, max(b[e] & 0x7fffu, (b[e] >> 16) & 0x7fffu));
+            for (int e = 0; e < 4; ++e) {
+                acc += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
+                amax = max(amax, max(b[e] & 0x7fffu, (b[e] >> 16) & 0x7fffu));
+            }
         }
-    }
 #pragma unroll
-    for (int m = 1; m < 16; m <<= 1) {
-        acc += __shfl_xor(acc, m, 64);
-        amax = max(amax, (uint32_t)__shfl_xor((int)amax, m, 64));
+        for (int m = 1; m < 16; m <<= 1) {
+            acc += __shfl_xor(acc, m, 64);
+            amax = max(amax, (uint32_t)__shfl_xor((int)amax, m, 64));
+        }
+        if (c == 0) {
+            const int tl = r / hq, h = r - tl * hq;
+            st[h * kStatTok + tl] = -acc;
+            st[(hq + h) * kStatTok + tl] = (float)shift_of(amax);
+        }
+        gmax = max(gmax, amax);
     }
-    if (row < n_rows && c == 0) {
-        const int t = (int)(row / hq), h = (int)(row % hq);
-        const int64_t at = (int64_t)h * T + t;
-        const int kq = shift_of(amax);
-        const float l2 = -lse[at] * kLog2e;
-        sc.Dq[at] = -acc;
-        sc.lse2q[at] = l2 + (float)kq;
-        sc.kqmul[at] = pow2i(-kq);
-        sc.lse2kv[at] = l2;
-    }
-    // the tensor's maximum: one atomic per wave at most, and none once the stored value has caught
-    // up (the plain read only filters; the atomic decides)
-    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 16, 64));
-    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32, 64));
-    if ((threadIdx.x & 63) == 0 && amax > __hip_atomic_load(sc.absmax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-        atomicMax(sc.absmax, amax);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Pass 2 (16 lanes per row): the fp16 copies of Q, dO * 2^kg and K, and Dkv = -D * 2^kg.
-// ---------------------------------------------------------------------------------------------
-template <int HD = kHeadDim>
-__global__ void __launch_bounds__(256) hyd_bwd_convert_bf16_kernel(const uint16_t* __restrict__ q,
-                                                                  const uint16_t* __restrict__ d_o,
-                                                                  const uint16_t* __restrict__ k,
-                                                                  BwdScratch sc, int T, int hq, int hkv) {
-    const int64_t n_rows = (int64_t)T * hq, n_kv = (int64_t)T * hkv;
-    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int c = threadIdx.x & 15;
-    const float up = pow2i(shift_of(*sc.absmax));
-    if (row < n_rows && (HD == kHeadDim || c < HD / 8)) {
-        const int64_t at = row * HD + c * 8;
-        const u32x4 a = *reinterpret_cast<const u32x4*>(q + at);
-        const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + at);
-        u32x4 a16, b16;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { a16[e] = bf16x2_to_f16x2(a[e]); b16[e] = bf16x2_to_f16x2(b[e], up); }
-        *reinterpret_cast<u32x4*>(sc.q16 + at) = a16;
-        *reinterpret_cast<u32x4*>(sc.do16 + at) = b16;
-        if (row < n_kv) {
+    for (int r = grp; r < nt * hkv; r += 16) {     // the K rows of the same tokens
+        if (lane_on) {
+            const int64_t at = ((int64_t)t0 * hkv + r) * HD + c * 8;
             const u32x4 x = *reinterpret_cast<const u32x4*>(k + at);
             u32x4 x16;
 #pragma unroll
@@ -128,15 +111,28 @@ __global__ void __launch_bounds__(256) hyd_bwd_convert_bf16_kernel(const uint16_
             *reinterpret_cast<u32x4*>(sc.k16 + at) = x16;
         }
     }
-    if (row < n_rows && c == 0) {
-        const int t = (int)(row / hq), h = (int)(row % hq);
-        const int64_t at = (int64_t)h * T + t;
-        sc.Dkv[at] = sc.Dq[at] * up;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < hq * kStatTok; idx += 256) {
+        const int h = idx / kStatTok, tl = idx % kStatTok;
+        if (tl < nt) {
+            const int64_t at = (int64_t)h * T + t0 + tl;
+            const float l2 = -lse[at] * kLog2e, kq = st[(hq + h) * kStatTok + tl];
+            sc.Dq[at] = st[idx];
+            sc.lse2q[at] = l2 + kq;
+            sc.kqmul[at] = pow2i(-(int)kq);
+            sc.lse2kv[at] = l2;
+        }
     }
+    // the tensor's maximum: one atomic per wave at most, and none once the stored value has caught
+    // up (the plain read only filters; the atomic decides)
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) gmax = max(gmax, (uint32_t)__shfl_xor((int)gmax, m, 64));
+    if ((threadIdx.x & 63) == 0 && gmax > __hip_atomic_load(sc.absmax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(sc.absmax, gmax);
 }
 
 struct BwdParams {
-    const uint16_t* v; const uint16_t* d_o;     // the caller's bf16 V and dO (Q, K and the scaled dO are read from sc)
+    const uint16_t* q; const uint16_t* v; const uint16_t* d_o;     // the caller's bf16 Q, V and dO (dQ kernel; dK/dV: V only)
     BwdScratch sc;
     uint16_t* dq; uint16_t* dk; uint16_t* dv;
     int T, hq, hkv;
@@ -157,6 +153,8 @@ struct BwdParams {
 // the bf16 MFMA, exact inputs either way).  The row's P carries the factor 2^kq that brings its dO
 // into fp16's range (it sits in -LSE2), so dS = P (dP - D) is formed for the scaled row and dQ is
 // scaled back by 2^-kq when it is written.
+// This kernel runs BEFORE dK/dV and, having every Q and dO row of its item in LDS once, also writes
+// what that kernel streams: the fp16 copies of Q and of dO * 2^kg, and -D * 2^kg.
 // ---------------------------------------------------------------------------------------------
 constexpr int kDqWaves = 8;
 constexpr int kDqBM = 32 * kDqWaves, kDqBN = 64, kDqThreads = 64 * kDqWaves;
@@ -273,6 +271,8 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
     // only the score product reads; a zero scale becomes an epsilon so that -inf * scale = -inf
     const float scale_log2 = fmaxf(fabsf(p.scale_log2), 1e-30f);
     const uint32_t sign_flip = p.scale_log2 < 0.f ? 0x80008000u : 0u;
+    const float up = pow2i(shift_of(*p.sc.absmax));                   // 2^kg
+    const bool wave_first_half = half == 0;                           // both halves of a wave hold the same rows
 
     WorkFetcher wf;
     WorkItem wi;
@@ -328,7 +328,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         {   // rows q0 .. q0+255 of Q and dO of this head; rows past the query range read as zeros
             const uint32_t q_bytes = (uint32_t)(min(Lq - q0, kDqBM) - 1) * q_stride_b + kRowB;
             const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * D;
-            dma_rows<kDqWaves>(make_rsrc(p.sc.q16 + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
+            dma_rows<kDqWaves>(make_rsrc(p.q + off, q_bytes), smem + kDqQxOff, [](int j) { return j * kDqTileBytes; },
                                kDqBM / 64, q_stride_b, wave, dma_voff_q);
             dma_rows<kDqWaves>(make_rsrc(p.d_o + off, q_bytes), smem + kDqStageBytes, [](int j) { return j * kDqTileBytes; },
                                kDqBM / 64, q_stride_b, wave, dma_voff_q);
@@ -338,6 +338,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
             lse2 = p.sc.lse2q[(int64_t)head * p.T + row0 + qrow];
             Dq = p.sc.Dq[(int64_t)head * p.T + row0 + qrow];
             unshift = p.sc.kqmul[(int64_t)head * p.T + row0 + qrow];
+            if (wave_first_half) p.sc.Dkv[(int64_t)head * p.T + row0 + qrow] = Dq * up;
         }
         f32x16 acc[D / 32];
 #pragma unroll
@@ -357,9 +358,38 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
 #pragma unroll
             for (int ks = 0; ks < D / 16; ++ks) {
                 asm volatile("" : "+v"(a[ks]), "+v"(b[ks]));      // the reads stay on this side of the barrier
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[ks][e] = bf16x2_to_f16x2(a[ks][e]);
                 qf[ks] = as_bf16x8(a[ks] ^ sign_flip);
                 dof[ks] = as_bf16x8(b[ks]);
             }
+        }
+        {   // fp16 copies of the item's rows for the dK/dV kernel: thread (row group tid / 16, chunk
+            // tid % 16) takes 16-byte pieces of whole rows out of the staging areas, so that every
+            // store instruction of a wave writes four whole rows
+            const int n_item = min(Lq - q0, kDqBM);
+            const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * D;
+            const int cr = tid >> 4, ch = tid & 15;
+            const uint32_t src = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)tile_off(cr, ch);
+#pragma unroll
+            for (int which = 0; which < 2; ++which) {
+                const uint32_t base = src + (which ? kDqStageBytes : kDqQxOff);
+                uint16_t* dst = (which ? p.sc.do16 : p.sc.q16) + off + (int64_t)cr * q_stride + ch * 8;
+                const float mul = which ? up : 1.f;
+                u32x4 x[kDqBM / 32];
+#pragma unroll
+                for (int i = 0; i < kDqBM / 32; ++i)         // row cr + 32 i: tile i / 2, row cr + 32 (i % 2) of it
+                    x[i] = *(lds_u32x4*)(uintptr_t)(base + (uint32_t)((i >> 1) * kDqTileBytes + (i & 1) * 32 * kRowBytes));
+#pragma unroll
+                for (int i = 0; i < kDqBM / 32; ++i) {
+                    u32x4 y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = bf16x2_to_f16x2(x[i][e], mul);
+                    if (cr + 32 * i < n_item && (D == kHeadDim || ch < D / 8))
+                        *reinterpret_cast<u32x4*>(dst + (int64_t)(32 * i) * q_stride) = y;
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0): the staging areas have been read
         }
         __builtin_amdgcn_s_barrier();                     // stages 1 and 2 may take K/V tiles now
         if (t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
