@@ -174,6 +174,50 @@ def per_buffer(cid, reps=5, warmup=2):
             "ms": ms, "useful_tflop": tf, "max_over_min_ms": max(ms) / min(ms), "sum_ms": sum(ms)}
 
 
+def rope_study(cid, reps=10, warmup=3):
+    """Position reset for Q (Sec. 2.1): the rotary embedding of Q applied inside the kernels
+    (hyd_varlen_attn_fwd_rope / _bwd_rope) against passes of their own over Q and dQ
+    (hyd_rope_packed before the forward, its inverse after the backward).  K is rotated by its own
+    pass either way and is not timed.  Median milliseconds of one forward + backward."""
+    import statistics
+    import torch
+    from paper_2412_07894_amd import binding, workloads as wl
+    cfg = wl.CONFIGS[cid]
+    lengths = wl.seqlens(cid)
+    q, k, v, do, cu = gpu_inputs(cfg, lengths, seed=1000 * cid)
+    ml = int(max(lengths))
+    q_rot, dq_un = torch.empty_like(q), torch.empty_like(q)
+
+    def timed(fn):
+        ms = []
+        for it in range(warmup + reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= warmup:
+                ms.append(e0.elapsed_time(e1))
+        return statistics.median(ms)
+
+    def fused():
+        o, lse = binding.varlen_attn_fwd(q, k, v, cu, ml, cfg.scale, rope_base=10000.0)
+        binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, cfg.scale, rope_base=10000.0)
+
+    def separate():
+        binding.rope_packed(q, cu, out=q_rot)
+        o, lse = binding.varlen_attn_fwd(q_rot, k, v, cu, ml, cfg.scale)
+        dq, _, _ = binding.varlen_attn_bwd(q_rot, k, v, o, lse, do, cu, ml, cfg.scale)
+        binding.rope_packed(dq, cu, inverse=True, out=dq_un)
+
+    def plain():
+        o, lse = binding.varlen_attn_fwd(q, k, v, cu, ml, cfg.scale)
+        binding.varlen_attn_bwd(q, k, v, o, lse, do, cu, ml, cfg.scale)
+
+    return {"config": cid, "ms_no_rotation": timed(plain), "ms_rotation_inside_the_kernels": timed(fused),
+            "ms_rotation_by_two_passes_over_q_and_dq": timed(separate)}
+
+
 def cpu_baseline(cid):
     """The fp64 oracle, as it stands, on a bounded sample of the workload (about 2-3e12 flop,
     10-30 s on 16 cores): as many KV groups as the oracle has threads (its OpenMP loop runs over
@@ -263,6 +307,7 @@ def main():
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--inputs", default="randn", choices=["randn", "zeros"])
     ap.add_argument("--per-buffer", action="store_true", help="also time one call per packed buffer")
+    ap.add_argument("--rope-study", action="store_true", help="also time the rotary embedding of Q inside the kernels against passes of its own")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU hot path (no collectives, no sharding); run with --gpus 1")
@@ -296,6 +341,8 @@ def main():
             out["mfma_probe"] = probe
     if args.per_buffer and head["dtype"] == "bf16":
         out["per_buffer"] = per_buffer(head["cid"])
+    if args.rope_study and head["dtype"] == "bf16":
+        out["rope_study"] = [rope_study(r["cid"]) for r in results if r["dtype"] == "bf16"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(head["cid"])
     print(json.dumps(out))

@@ -135,6 +135,35 @@ hyd_status hyd_varlen_attn_bwd(const void* q, const void* k, const void* v, cons
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward and backward with the rotary position embedding of Q applied inside the kernels.
+ * Packing requires positions that restart in every packed sequence (paper Sec. 2.1, the packing
+ * paragraph); the kernels know the local position of every query row, so Q needs no pass of its
+ * own through HBM: `q` is the UNROTATED Q, rotated as a work item picks its rows up (pairing,
+ * angles and `rope_base` as in hyd_rope_packed below, position = row index inside its sequence).
+ * `k` must already be rotated (one hyd_rope_packed call per layer: every query tile of a sequence
+ * streams K again, rotating it there would repeat the work).  The backward returns dQ for the
+ * unrotated Q (it turns the gradient back before writing it) and dK for the rotated K that was
+ * passed in (apply hyd_rope_packed with inverse = 1 to it for the gradient of the unrotated K).
+ * bf16 only (else HYD_ERR_DTYPE); rope_base must exceed 1 (else HYD_ERR_SHAPE); everything else
+ * as hyd_varlen_attn_fwd / hyd_varlen_attn_bwd, including the workspace sizes.
+ */
+hyd_status hyd_varlen_attn_fwd_rope(const void* q, const void* k, const void* v,
+                                    const int32_t* cu_seqlens, int num_seqs,
+                                    const int32_t* cu_seqlens_host,
+                                    int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                                    float softmax_scale, float rope_base, hyd_dtype dt,
+                                    void* o, float* lse,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+hyd_status hyd_varlen_attn_bwd_rope(const void* q, const void* k, const void* v, const void* o,
+                                    const float* lse, const void* d_o,
+                                    const int32_t* cu_seqlens, int num_seqs,
+                                    const int32_t* cu_seqlens_host,
+                                    int total_tokens, int max_seqlen, int hq, int hkv, int head_dim,
+                                    float softmax_scale, float rope_base, hyd_dtype dt,
+                                    void* dq, void* dk, void* dv,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * What the schedule prelude of the last forward (is_bwd = 0) or backward (is_bwd = 1) call on
  * `workspace` saw in the DEVICE cu_seqlens.  The entry points above cannot look at device memory
  * without stalling the stream, so with cu_seqlens_host == NULL they trust the caller: a sequence

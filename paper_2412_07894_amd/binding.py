@@ -18,6 +18,7 @@ EXPORTS = (
     "hyd_varlen_attn_fwd_range", "hyd_varlen_attn_bwd_range", "hyd_attn_merge", "hyd_rope_packed",
     "hyd_varlen_attn_fwd_noalloc", "hyd_varlen_attn_fwd_noalloc_max_workspace",
     "hyd_varlen_attn_schedule_status", "hyd_varlen_attn_schedule_layout",
+    "hyd_varlen_attn_fwd_rope", "hyd_varlen_attn_bwd_rope",
 )
 RANGE_ALIGN = 256   # HYD_RANGE_ALIGN of the header
 
@@ -54,6 +55,11 @@ def load():
     lib.hyd_varlen_attn_schedule_layout.restype = i
     lib.hyd_varlen_attn_schedule_layout.argtypes = [i, i, i, i, i, i, i, i, ctypes.POINTER(sz), ctypes.POINTER(sz),
                                                     ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.hyd_varlen_attn_fwd_rope.restype = i
+    lib.hyd_varlen_attn_fwd_rope.argtypes = [vp, vp, vp, ip, i, ip, i, i, i, i, i, f, f, i, vp, vp, vp, sz, vp]
+    lib.hyd_varlen_attn_bwd_rope.restype = i
+    lib.hyd_varlen_attn_bwd_rope.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, f, i,
+                                             vp, vp, vp, vp, sz, vp]
     lib.hyd_varlen_attn_bwd.restype = i
     lib.hyd_varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, i, ip, i, i, i, i, i, f, i,
                                         vp, vp, vp, vp, sz, vp]
@@ -115,9 +121,10 @@ def _stream_ptr(stream):
 
 
 def varlen_attn_fwd(q, k, v, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_host=None,
-                    workspace=None, stream=None, out=None, lse=None):
+                    workspace=None, stream=None, out=None, lse=None, rope_base=None):
     """q[T,Hq,d], k,v[T,Hkv,d] contiguous device tensors (bf16 or fp32); cu_seqlens int32 device
-    tensor [num_seqs+1].  Returns (o[T,Hq,d], lse[Hq,T] fp32)."""
+    tensor [num_seqs+1].  Returns (o[T,Hq,d], lse[Hq,T] fp32).  With rope_base the call is
+    hyd_varlen_attn_fwd_rope: q unrotated (rotated inside the kernel), k already rotated."""
     lib = load()
     T, hq, d = q.shape
     hkv = k.shape[1]
@@ -130,10 +137,16 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_h
     need = workspace_bytes(T, nseq, hq, hkv, d, dt, False)
     ws = _workspace(need, q.device) if workspace is None else workspace
     keep, hp = _host_ptr(cu_seqlens_host)
-    _check(lib.hyd_varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(), nseq,
-                                   hp, T, int(max_seqlen), hq, hkv, d, float(softmax_scale), dt,
-                                   o.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
-                                   _stream_ptr(stream)))
+    if rope_base is None:
+        _check(lib.hyd_varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(), nseq,
+                                       hp, T, int(max_seqlen), hq, hkv, d, float(softmax_scale), dt,
+                                       o.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       _stream_ptr(stream)))
+    else:
+        _check(lib.hyd_varlen_attn_fwd_rope(q.data_ptr(), k.data_ptr(), v.data_ptr(), cu_seqlens.data_ptr(), nseq,
+                                            hp, T, int(max_seqlen), hq, hkv, d, float(softmax_scale), float(rope_base), dt,
+                                            o.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
+                                            _stream_ptr(stream)))
     return o, lse
 
 
@@ -154,8 +167,9 @@ def varlen_attn_fwd_noalloc(q, k, v, cu_seqlens, max_seqlen, softmax_scale, out,
 
 
 def varlen_attn_bwd(q, k, v, o, lse, d_o, cu_seqlens, max_seqlen, softmax_scale, cu_seqlens_host=None,
-                    workspace=None, stream=None, dq=None, dk=None, dv=None):
-    """Returns (dq, dk, dv) with the shapes and dtype of q, k, v."""
+                    workspace=None, stream=None, dq=None, dk=None, dv=None, rope_base=None):
+    """Returns (dq, dk, dv) with the shapes and dtype of q, k, v.  With rope_base the call is
+    hyd_varlen_attn_bwd_rope: q unrotated, k rotated; dq is for the unrotated q, dk for the rotated k."""
     lib = load()
     T, hq, d = q.shape
     hkv = k.shape[1]
@@ -169,10 +183,16 @@ def varlen_attn_bwd(q, k, v, o, lse, d_o, cu_seqlens, max_seqlen, softmax_scale,
     need = workspace_bytes(T, nseq, hq, hkv, d, dt, True)
     ws = _workspace(need, q.device) if workspace is None else workspace
     keep, hp = _host_ptr(cu_seqlens_host)
-    _check(lib.hyd_varlen_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-                                   d_o.data_ptr(), cu_seqlens.data_ptr(), nseq, hp, T, int(max_seqlen),
-                                   hq, hkv, d, float(softmax_scale), dt, dq.data_ptr(), dk.data_ptr(),
-                                   dv.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    if rope_base is None:
+        _check(lib.hyd_varlen_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                       d_o.data_ptr(), cu_seqlens.data_ptr(), nseq, hp, T, int(max_seqlen),
+                                       hq, hkv, d, float(softmax_scale), dt, dq.data_ptr(), dk.data_ptr(),
+                                       dv.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    else:
+        _check(lib.hyd_varlen_attn_bwd_rope(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                            d_o.data_ptr(), cu_seqlens.data_ptr(), nseq, hp, T, int(max_seqlen),
+                                            hq, hkv, d, float(softmax_scale), float(rope_base), dt, dq.data_ptr(),
+                                            dk.data_ptr(), dv.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return dq, dk, dv
 
 

@@ -31,8 +31,9 @@ struct SchedLayout { size_t hdr, lev, order, items; int n_lev, max_items; };
 struct WsLayout {
     SchedLayout sched[2];
     int n_sched;
-    size_t stat[kBwdStatVecs], q16, do16, k16, total;
+    size_t stat[kBwdStatVecs], q16, do16, k16, rope_tab, total;
 };
+constexpr int kRopeTabEntries = 64;       // head_dim / 2 at most
 
 size_t sched_layout(SchedLayout& v, size_t at, int T, int nseq, int tile) {
     v.n_lev = (T + tile - 1) / tile;
@@ -60,6 +61,7 @@ WsLayout ws_layout(int T, int nseq, int tile0, int tile1, int hq, int hkv, int h
     w.q16 = at;  if (copies) at += align_up(2 * (size_t)T * (size_t)hq * (size_t)head_dim);
     w.do16 = at; if (copies) at += align_up(2 * (size_t)T * (size_t)hq * (size_t)head_dim);
     w.k16 = at;  if (copies) at += align_up(2 * (size_t)T * (size_t)hkv * (size_t)head_dim);
+    w.rope_tab = at; at += align_up(sizeof(double) * kRopeTabEntries);       // rotary frequency table (the *_rope calls)
     w.total = at;
     return w;
 }
@@ -291,12 +293,14 @@ size_t hyd_varlen_attn_workspace_bytes(int total_tokens, int num_seqs, int hq, i
 namespace {
 
 // forward of the plain entry point (ranges == NULL) and of the range variant
+// rope_base: 0 = no rotation, else the base of the rotary embedding applied to Q inside the kernels
 hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                     int num_seqs, const int32_t* cu_seqlens_host, const int32_t* ranges,
                     const int32_t* ranges_host, bool ranged, int total_tokens,
                     int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
                     hyd_dtype dt, void* o, float* lse, void* workspace,
-                    size_t workspace_bytes, void* hip_stream) {
+                    size_t workspace_bytes, void* hip_stream, float rope_base = 0.f) {
+    if (rope_base != 0.f && (dt != HYD_BF16 || !(rope_base > 1.f))) return dt != HYD_BF16 ? HYD_ERR_DTYPE : HYD_ERR_SHAPE;
     const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
                                           hq, hkv, head_dim, dt, workspace, workspace_bytes, false);
     if (vs != HYD_OK) return vs;
@@ -315,9 +319,11 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
     const int tile = tile_fwd(dt);
     const WsLayout w = ws_layout(total_tokens, num_seqs, tile, tile, hq, hkv, head_dim, dt, false);
     const SchedView sv = make_view(static_cast<char*>(workspace), w.sched[0], tile, max_seqlen);
+    double* rope_tab = rope_base != 0.f ? reinterpret_cast<double*>(static_cast<char*>(workspace) + w.rope_tab) : nullptr;
     {
         KernelTimer kt("schedule_prelude", st);
-        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, total_tokens, tile, sv, tile, sv);
+        hipLaunchKernelGGL(hyd_schedule_prelude, dim3(1), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, total_tokens, tile, sv, tile, sv,
+                           rope_tab, head_dim / 2, rope_base != 0.f ? log2((double)rope_base) : 0.0);
     }
     const HeadMap hm = head_map_q(hq, hkv);
     const long long work = (long long)sv.max_items * hq;
@@ -329,6 +335,7 @@ hyd_status fwd_impl(const void* q, const void* k, const void* v, const int32_t* 
         p.scale_log2 = softmax_scale * kLog2e;
         p.hdr = sv.hdr; p.cursors = sv.hdr + kHdrCursor; p.items = sv.items; p.hm = hm; p.tr = t_trace;
         p.ranges = ranged ? ranges : nullptr;
+        p.rope_tab = rope_tab;
         const dim3 grid(persistent_grid(*dev, dev->occ_fwd, work));
         KernelTimer kt(ranged ? "fwd_range_bf16" : "fwd_bf16", st);
         if (head_dim == 64) {
@@ -357,7 +364,8 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
                     const int32_t* cu_seqlens_host, const int32_t* ranges, const int32_t* ranges_host,
                     bool ranged, int total_tokens, int max_seqlen, int hq,
                     int hkv, int head_dim, float softmax_scale, hyd_dtype dt, void* dq, void* dk,
-                    void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                    void* dv, void* workspace, size_t workspace_bytes, void* hip_stream, float rope_base = 0.f) {
+    if (rope_base != 0.f && (dt != HYD_BF16 || !(rope_base > 1.f))) return dt != HYD_BF16 ? HYD_ERR_DTYPE : HYD_ERR_SHAPE;
     const hyd_status vs = validate_common(cu_seqlens, num_seqs, cu_seqlens_host, total_tokens, max_seqlen,
                                           hq, hkv, head_dim, dt, workspace, workspace_bytes, true);
     if (vs != HYD_OK) return vs;
@@ -378,12 +386,13 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     const SchedView sv_kv = make_view(ws, w.sched[0], tile_kv(dt), max_seqlen);
     const SchedView sv_q = make_view(ws, w.sched[1], tile_dq(dt), max_seqlen);
     float* Dvec = reinterpret_cast<float*>(ws + w.stat[0]);
+    double* rope_tab = rope_base != 0.f ? reinterpret_cast<double*>(ws + w.rope_tab) : nullptr;
     // one launch builds the item list of the dK/dV kernel and, if the dQ kernel uses another tile
     // size, the dQ kernel's too (one workgroup each)
     {
         KernelTimer kt("schedule_prelude", st);
         hipLaunchKernelGGL(hyd_schedule_prelude, dim3(w.n_sched), dim3(kPreludeThreads), 0, st, cu_seqlens, num_seqs, total_tokens,
-                           tile_kv(dt), sv_kv, tile_dq(dt), sv_q);
+                           tile_kv(dt), sv_kv, tile_dq(dt), sv_q, rope_tab, head_dim / 2, rope_base != 0.f ? log2((double)rope_base) : 0.0);
     }
     const long long n_rows = (long long)total_tokens * hq;
     const long long work_q = (long long)sv_q.max_items * hq, work_kv = (long long)sv_kv.max_items * hkv;
@@ -416,6 +425,7 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
         p.scale = softmax_scale; p.scale_log2 = softmax_scale * kLog2e;
         p.tr = t_trace;
         p.ranges = ranged ? ranges : nullptr;
+        p.rope_tab = rope_tab;
         // dQ first: it also writes the fp16 copies of Q and dO that dK/dV streams
         {
             p.hdr = sv_q.hdr; p.items = sv_q.items;
@@ -485,6 +495,29 @@ hyd_status hyd_varlen_attn_fwd(const void* q, const void* k, const void* v, cons
     return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false, total_tokens,
                     max_seqlen, hq, hkv, head_dim, softmax_scale, dt, o, lse, workspace, workspace_bytes,
                     hip_stream);
+}
+
+hyd_status hyd_varlen_attn_fwd_rope(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                                    int num_seqs, const int32_t* cu_seqlens_host, int total_tokens,
+                                    int max_seqlen, int hq, int hkv, int head_dim, float softmax_scale,
+                                    float rope_base, hyd_dtype dt, void* o, float* lse, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+    if (!(rope_base > 1.f)) return HYD_ERR_SHAPE;
+    return fwd_impl(q, k, v, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false, total_tokens,
+                    max_seqlen, hq, hkv, head_dim, softmax_scale, dt, o, lse, workspace, workspace_bytes,
+                    hip_stream, rope_base);
+}
+
+hyd_status hyd_varlen_attn_bwd_rope(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                    const void* d_o, const int32_t* cu_seqlens, int num_seqs,
+                                    const int32_t* cu_seqlens_host, int total_tokens, int max_seqlen, int hq,
+                                    int hkv, int head_dim, float softmax_scale, float rope_base, hyd_dtype dt,
+                                    void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+    if (!(rope_base > 1.f)) return HYD_ERR_SHAPE;
+    return bwd_impl(q, k, v, o, lse, d_o, cu_seqlens, num_seqs, cu_seqlens_host, nullptr, nullptr, false,
+                    total_tokens, max_seqlen, hq, hkv, head_dim, softmax_scale, dt, dq, dk, dv, workspace,
+                    workspace_bytes, hip_stream, rope_base);
 }
 
 size_t hyd_varlen_attn_fwd_noalloc_max_workspace(void) { return kScratchBytes; }

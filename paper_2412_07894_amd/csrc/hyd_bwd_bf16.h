@@ -141,6 +141,8 @@ struct BwdParams {
     HeadMap hm;
     WgTrace tr;
     const int32_t* ranges;            // range variants only: per sequence (q_begin, q_end, kv_begin, kv_end)
+    const double* rope_tab;           // NULL, or the rotary frequency table: the dQ kernel rotates Q as it picks it up
+                                      // (the fp16 copy it writes is the rotated Q) and turns dQ back before writing it
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -356,40 +358,54 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0)
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                asm volatile("" : "+v"(a[ks]), "+v"(b[ks]));      // the reads stay on this side of the barrier
+            for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(a[ks]), "+v"(b[ks]));      // the reads stay on this side of the barrier
+            // Q -> fp16, rotated first if the call asks for it (position = local row: reset per sequence)
+            if (p.rope_tab) {
+                rope_row_frags<D, true>(a, p.rope_tab, qrow, half);
+            } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[ks][e] = bf16x2_to_f16x2(a[ks][e]);
+                for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[ks][e] = bf16x2_to_f16x2(a[ks][e]);
+            }
+            // What the dK/dV kernel streams: the fp16 Q rows and dO * 2^kg.  Each wave puts its 32 rows
+            // back where it took them from (nobody else touches those bytes) and sends them out from
+            // there in 16-byte pieces of whole rows: four whole rows per store instruction.
+            typedef __attribute__((address_space(3))) u32x4 lds_u32x4_w;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) {
+                u32x4 s16;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s16[e] = bf16x2_to_f16x2(b[ks][e], up);
+                *(lds_u32x4_w*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqQxOff + row_stage)) = a[ks];
+                *(lds_u32x4_w*)(uintptr_t)(fa.row[ks] + (uint32_t)(kDqStageBytes + row_stage)) = s16;
+            }
+            // (the lane index is laundered so that these addresses are formed here: hoisted above the
+            // tile loop as lane constants they would occupy some 20 registers through it)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int cr = ln >> 4, ch = ln & 15;
+            const uint32_t wbase = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)(row_stage + cr * kRowBytes);
+            const int64_t goff = (int64_t)(row0 + wrow0 + cr) * q_stride + (int64_t)head * D + ch * 8;
+#pragma unroll
+            for (int which = 0; which < 2; ++which) {
+                uint16_t* dst = (which ? p.sc.do16 : p.sc.q16) + goff;
+                u32x4 x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)                 // row cr + 4 i of the wave: swz = (cr << 2) | (i & 3)
+                    x[i] = *(lds_u32x4*)(uintptr_t)(wbase + (uint32_t)((which ? kDqStageBytes : kDqQxOff) + 4 * i * kRowBytes +
+                                                                      ((ch ^ ((cr << 2) | (i & 3))) << 4)));
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (wrow0 + cr + 4 * i < Lq && (D == kHeadDim || ch < D / 8))
+                        *reinterpret_cast<u32x4*>(dst + (int64_t)(4 * i) * q_stride) = x[i];
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0): the staging areas have been read
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) {
                 qf[ks] = as_bf16x8(a[ks] ^ sign_flip);
                 dof[ks] = as_bf16x8(b[ks]);
             }
-        }
-        {   // fp16 copies of the item's rows for the dK/dV kernel: thread (row group tid / 16, chunk
-            // tid % 16) takes 16-byte pieces of whole rows out of the staging areas, so that every
-            // store instruction of a wave writes four whole rows
-            const int n_item = min(Lq - q0, kDqBM);
-            const int64_t off = (int64_t)(row0 + q0) * q_stride + (int64_t)head * D;
-            const int cr = tid >> 4, ch = tid & 15;
-            const uint32_t src = (uint32_t)(uintptr_t)(lds_char*)smem + (uint32_t)tile_off(cr, ch);
-#pragma unroll
-            for (int which = 0; which < 2; ++which) {
-                const uint32_t base = src + (which ? kDqStageBytes : kDqQxOff);
-                uint16_t* dst = (which ? p.sc.do16 : p.sc.q16) + off + (int64_t)cr * q_stride + ch * 8;
-                const float mul = which ? up : 1.f;
-                u32x4 x[kDqBM / 32];
-#pragma unroll
-                for (int i = 0; i < kDqBM / 32; ++i)         // row cr + 32 i: tile i / 2, row cr + 32 (i % 2) of it
-                    x[i] = *(lds_u32x4*)(uintptr_t)(base + (uint32_t)((i >> 1) * kDqTileBytes + (i & 1) * 32 * kRowBytes));
-#pragma unroll
-                for (int i = 0; i < kDqBM / 32; ++i) {
-                    u32x4 y;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] = bf16x2_to_f16x2(x[i][e], mul);
-                    if (cr + 32 * i < n_item && (D == kHeadDim || ch < D / 8))
-                        *reinterpret_cast<u32x4*>(dst + (int64_t)(32 * i) * q_stride) = y;
-                }
-            }
-            __builtin_amdgcn_s_waitcnt(0xc07f);           // lgkmcnt(0): the staging areas have been read
         }
         __builtin_amdgcn_s_barrier();                     // stages 1 and 2 may take K/V tiles now
         if (t_lo + 1 < n_kt) dma_tile(t_lo + 1, 1);
@@ -421,6 +437,7 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
             if (t + 1 < n_kt) step(std::integral_constant<int, 1>{}, t + 1);
             if (t + 2 < n_kt) step(std::integral_constant<int, 2>{}, t + 2);
         }
+        if (active && p.rope_tab) rope_acc_inverse<D>(acc, p.rope_tab, qrow, half);     // gradient of the UNROTATED Q
         if (active)         // dQ leaves through this wave's 8 KB of the ring (free now): whole rows per store
             store_rows_via_lds<D>(p.dq + (int64_t)(row0 + wrow0) * q_stride + (int64_t)head * D, q_stride, Lq - wrow0,
                                acc, p.scale * unshift, o_stage, lane);

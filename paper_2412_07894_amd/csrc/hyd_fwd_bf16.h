@@ -55,6 +55,7 @@ struct FwdParams {
     HeadMap hm;
     WgTrace tr;
     const int32_t* ranges;            // range variant only: per sequence (q_begin, q_end, kv_begin, kv_end)
+    const double* rope_tab;           // NULL, or the rotary frequency table: Q rows are rotated as they are picked up
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -280,8 +281,10 @@ __global__ void __launch_bounds__(kFwdThreads, 1) hyd_fwd_bf16_kernel(FwdParams 
 #pragma unroll
             for (int ks = 0; ks < D / 16; ++ks) {
                 asm volatile("" : "+v"(qv[ks]));          // the reads stay on this side of the barrier
-                qf[ks] = as_bf16x8(qv[ks] ^ sign_flip);
             }
+            if (p.rope_tab) rope_row_frags<D, false>(qv, p.rope_tab, qrow, half);      // position = local row: reset per sequence
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) qf[ks] = as_bf16x8(qv[ks] ^ sign_flip);
         }
         __builtin_amdgcn_s_barrier();                     // the staged Q may be overwritten (tile t_lo+2 goes there)
 

@@ -15,6 +15,7 @@
 // queues empty and no workgroup waits on another.
 #pragma once
 #include "hyd_device.h"
+#include "hyd_rope_regs.h"
 
 namespace hyd {
 
@@ -71,8 +72,12 @@ constexpr int kPreludeLdsLev = 4096;      // levels whose arrays fit the kernel'
 // come from one launch.  n_lev* bounds the tiles per sequence (from the caller's max_seqlen).
 // Order among items of equal cost: by sequence rank (arrival order among equals), which is
 // unspecified (it never changes a result: every output element has exactly one producer).
+// With rope_tab != NULL the first workgroup also fills the rotary frequency table of the call
+// (half_d entries, see hyd_rope_regs.h).
 __global__ void __launch_bounds__(kPreludeThreads) hyd_schedule_prelude(const int32_t* __restrict__ cu, int nseq, int T,
-                                                                       int tile0, SchedView sv0, int tile1, SchedView sv1) {
+                                                                       int tile0, SchedView sv0, int tile1, SchedView sv1,
+                                                                       double* rope_tab, int half_d, double log2_base) {
+    if (rope_tab && blockIdx.x == 0) rope_table_fill(rope_tab, half_d, log2_base, threadIdx.x, kPreludeThreads);
     __shared__ int lds_lev[3 * (kPreludeLdsLev + 2)];
     const bool second = blockIdx.x != 0;
     const int tile = second ? tile1 : tile0;

@@ -208,3 +208,20 @@ def test_schedule_layout_and_status_argument_errors(lib):
     st = lambda ws, nbytes, T=1000, n=3, hq=8: lib.hyd_varlen_attn_schedule_status(ws, sz(nbytes), T, n, hq, 2, 128, 0, 0, None)
     assert st(None, 1 << 20) == 7 and st(P, 16) == 7 and st(P, 1 << 20, hq=7) == 4 and st(P, 1 << 20, T=-5) == 2
     assert st(None, 0, T=0, n=0) == 0
+
+
+def test_rope_variants_argument_errors(lib):
+    P = ctypes.c_void_p(1 << 20)
+    f = ctypes.c_float
+    lib.hyd_varlen_attn_fwd_rope.restype = ctypes.c_int
+    lib.hyd_varlen_attn_bwd_rope.restype = ctypes.c_int
+    fwd = lambda base, dt=0: lib.hyd_varlen_attn_fwd_rope(P, P, P, P, 3, None, 1000, 500, 8, 2, 128, f(0.1), f(base), dt, P, P, P,
+                                                         ctypes.c_size_t(1 << 30), None)
+    bwd = lambda base, dt=0: lib.hyd_varlen_attn_bwd_rope(P, P, P, P, P, P, P, 3, None, 1000, 500, 8, 2, 128, f(0.1), f(base), dt,
+                                                         P, P, P, P, ctypes.c_size_t(1 << 30), None)
+    assert fwd(1.0) == 2 and fwd(0.0) == 2 and bwd(-3.0) == 2       # the base must exceed 1
+    assert fwd(10000.0, dt=1) == 3 and bwd(10000.0, dt=1) == 3     # bf16 only
+    # (a call with valid arguments is never made here: these pointers are fake)
+    Pn = None
+    assert lib.hyd_varlen_attn_fwd_rope(Pn, P, P, P, 3, None, 1000, 500, 8, 2, 128, f(0.1), f(10000.0), 0, P, P, P,
+                                        ctypes.c_size_t(1 << 30), None) == 1
