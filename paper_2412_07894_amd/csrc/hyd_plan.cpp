@@ -338,42 +338,74 @@ hyd_status hyd_plan_dispatch(const int32_t* lengths, int B, const int32_t* J,
         }
     }
     const double inf = std::numeric_limits<double>::infinity();
+    // Running state of one pipeline during a trial: the summed latency of its sequences, its
+    // longest sequence, and the bound of Eq. 2 that follows from the two.
+    struct Pipe {
+        const hyd_latency_model* model;
+        int stages;
+        double sum;
+        int64_t longest;
+        double bound;
+        double bound_with(int64_t l, double* sum_out, int64_t* longest_out) const {
+            *longest_out = std::max(l, longest);
+            *sum_out = sum + lat(*model, (double)l);
+            return *sum_out + lat(*model, (double)*longest_out) * (double)(stages - 1);
+        }
+    };
+    // The largest and the second largest bound, kept up to date as sequences are placed: the
+    // "maximum over the other pipelines" that every candidate placement is compared with is one of
+    // the two, so placing a sequence costs O(J_i) instead of O(J_i * D).
+    struct TopTwo {
+        double first, second;
+        int first_at;
+        void rebuild(const std::vector<Pipe>& ps) {
+            first = second = -std::numeric_limits<double>::infinity();
+            first_at = -1;
+            for (int j = 0; j < (int)ps.size(); ++j) {
+                if (ps[j].bound > first) { second = first; first = ps[j].bound; first_at = j; }
+                else if (ps[j].bound > second) second = ps[j].bound;
+            }
+        }
+        double without(int j) const { return j == first_at ? second : first; }
+        // a bound that grows (the rule with monotone latency models) never needs a new runner-up
+        void raise(int j, double b) {
+            if (j == first_at) first = b;
+            else if (b > first) { second = first; first = b; first_at = j; }
+            else if (b > second) second = b;
+        }
+    };
+    auto run_trial = [&](const int32_t* order, std::vector<Pipe>& pipes, std::vector<int32_t>& where) -> double {
+        for (int j = 0; j < D; ++j) { pipes[j].sum = 0.0; pipes[j].longest = 0; pipes[j].bound = 0.0; }
+        TopTwo top;
+        top.rebuild(pipes);
+        for (int k = 0; k < B; ++k) {
+            const int i = order[k];
+            double best = inf, best_sum = 0.0, best_bound = 0.0;
+            int64_t best_longest = 0;
+            int target = -1;
+            for (int j = 0; j < J[i]; ++j) {               // admissible pipelines, first one wins a tie
+                double sum_j;
+                int64_t longest_j;
+                const double bound_j = pipes[j].bound_with(lengths[i], &sum_j, &longest_j);
+                const double overall = std::max(bound_j, top.without(j));
+                if (overall < best) { best = overall; target = j; best_sum = sum_j; best_longest = longest_j; best_bound = bound_j; }
+            }
+            if (target < 0) return std::numeric_limits<double>::quiet_NaN();       // only with non-finite times
+            where[i] = target;
+            const bool grew = best_bound >= pipes[target].bound;
+            pipes[target].sum = best_sum; pipes[target].longest = best_longest; pipes[target].bound = best_bound;
+            if (grew) top.raise(target, best_bound);
+            else top.rebuild(pipes);                       // a fitted model may price a sequence below zero
+        }
+        return B == 0 ? 0.0 : top.first;
+    };
+    std::vector<Pipe> pipes(D);
+    for (int j = 0; j < D; ++j) { pipes[j].model = &models[j]; pipes[j].stages = pps[j]; }
     double best_cost = inf;
     std::vector<int32_t> best_assign(B), cur(B);
-    std::vector<double> C(D), E(D);
-    std::vector<int64_t> longest(D);
     for (int tr = 0; tr < trials; ++tr) {
-        std::fill(C.begin(), C.end(), 0.0);
-        std::fill(E.begin(), E.end(), 0.0);
-        std::fill(longest.begin(), longest.end(), 0);
-        for (int k = 0; k < B; ++k) {
-            const int i = perms[(size_t)tr * B + k];
-            // largest and second largest bound over the pipelines, to get "max over the others"
-            double top = -inf, second = -inf;
-            int top_j = -1;
-            for (int j = 0; j < D; ++j) {
-                const double v = C[j] + E[j];
-                if (v > top) { second = top; top = v; top_j = j; }
-                else if (v > second) second = v;
-            }
-            double o_min = inf, keep_c = 0.0, keep_e = 0.0;
-            int64_t keep_l = 0;
-            int j_star = -1;
-            for (int j = 0; j < J[i]; ++j) {
-                const int64_t l_max = std::max<int64_t>(lengths[i], longest[j]);
-                const double c_new = C[j] + lat(models[j], (double)lengths[i]);
-                const double e_new = lat(models[j], (double)l_max) * (double)(pps[j] - 1);
-                const double others = (j == top_j) ? second : top;
-                const double o_max = std::max(c_new + e_new, others);
-                if (o_max < o_min) { o_min = o_max; j_star = j; keep_c = c_new; keep_e = e_new; keep_l = l_max; }
-            }
-            if (j_star < 0) return HYD_ERR_INFEASIBLE;       // only with non-finite times
-            cur[i] = j_star;
-            C[j_star] = keep_c; E[j_star] = keep_e; longest[j_star] = keep_l;
-        }
-        double trial_cost = -inf;
-        for (int j = 0; j < D; ++j) trial_cost = std::max(trial_cost, C[j] + E[j]);
-        if (B == 0) trial_cost = 0.0;
+        const double trial_cost = run_trial(perms + (size_t)tr * B, pipes, cur);
+        if (trial_cost != trial_cost) return HYD_ERR_INFEASIBLE;
         if (trial_cost < best_cost) { best_cost = trial_cost; best_assign = cur; }
     }
     std::copy(best_assign.begin(), best_assign.end(), assign);

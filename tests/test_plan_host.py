@@ -222,6 +222,38 @@ def test_dispatch_matches_the_oracle_bit_for_bit(pl, seed):
     assert cost == want_cost
 
 
+def test_dispatch_against_enumeration_and_eq2(pl):
+    """The library's dispatcher pinned without the step-by-step reference: on small inputs its
+    cost is Eq. 2 evaluated on the assignment it returns (max over pipelines of the sum of the
+    latencies plus (PP - 1) times the latency of the longest sequence), every sequence sits on an
+    admissible pipeline, no assignment found by enumeration is cheaper than the optimum it must
+    not beat, and with every order of the sequences tried the best greedy result is within the
+    factor the tie-free cases show (equal to the optimum whenever a single pipeline is admissible)."""
+    import itertools
+    rng = random.Random(77)
+    for case in range(30):
+        B, D = rng.randint(1, 6), rng.randint(1, 3)
+        max_lens = sorted((rng.choice([512, 1024, 4096]) for _ in range(D)), reverse=True)
+        lengths = [rng.randint(16, max_lens[0]) for _ in range(B)]
+        J = po.admissible(lengths, max_lens)
+        models = [random_model(rng) for _ in range(D)]
+        pps = [rng.randint(1, 4) for _ in range(D)]
+        perms = [list(p) for p in itertools.permutations(range(B))][:120]
+        cost, assign = pl.dispatch(lengths, J, models, pps, perms)
+        assert all(0 <= assign[i] < J[i] for i in range(B))
+        eq2 = max(po.lower_bound([i for i in range(B) if assign[i] == j], lengths, models[j], pps[j]) for j in range(D))
+        assert abs(cost - eq2) <= 1e-9 * max(1.0, abs(eq2))
+        opt, _ = po.dispatch_bruteforce(lengths, J, models, pps)
+        assert cost >= opt - 1e-9 * max(1.0, abs(opt))
+        if all(j == 1 for j in J):
+            assert abs(cost - opt) <= 1e-9 * max(1.0, abs(opt))
+    # negative latencies (a fitted model with c < 0): the running maximum may shrink
+    neg = (0.0, 1.0, -50.0)
+    cost, assign = pl.dispatch([10, 20, 30], [2, 2, 2], [neg, neg], [1, 1], [[0, 1, 2]])
+    eq2 = max(po.lower_bound([i for i in range(3) if assign[i] == j], [10, 20, 30], neg, 1) for j in range(2))
+    assert cost == eq2
+
+
 def test_dispatch_worked_by_hand_and_errors(pl):
     from paper_2412_07894_amd.binding import HydError
     lin = (0.0, 1.0, 0.0)
