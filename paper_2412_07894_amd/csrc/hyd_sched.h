@@ -20,6 +20,7 @@
 namespace hyd {
 
 constexpr int kQueues = 8;
+
 constexpr int kHdrInts = 64;
 // header (ints): [0] n_items, [1] kSched* flags about cu_seqlens as the prelude saw it,
 // [8 + 8*k + x] cursor of queue x of kernel k (k = 0 fwd, 1 dK/dV, 2 dQ); the rest is zeroed by
@@ -143,15 +144,33 @@ __device__ __forceinline__ int queue_size(const HeadMap& hm, int n_items, int x)
     return n_items * hm.hpq;
 }
 
-// Work index w of queue x -> (item index, head).
-__device__ __forceinline__ void decode_work(const HeadMap& hm, int x, int w, int& item, int& head) {
+// Work index w of queue x -> (item index, head).  A partitioned queue walks the item list in
+// chunks of chunk_items() items (the list is ordered by decreasing cost, so a chunk holds items of
+// similar cost, in a long sequence neighbouring tiles) and, inside a chunk, one head group after
+// the other.  The 32 workgroups of an XCD then sit on neighbouring tiles of ONE KV head (times its
+// group's query heads) and share the K/V (or Q/dO) tiles they stream in their L2; with the heads
+// interleaved per item, a queue with several groups (MHA: every head is its own group) split
+// its workgroups over all of them and shared each stream among a fifth as many.  Walking whole
+// groups one after the other would share as well but starts the last group's longest items late,
+// which unbalances the end of a short launch; chunks keep the order longest-first up to a window
+// of one chunk, an eighth of the list at most.  Measured (one process, both orders alternating):
+// the MHA configuration 3 gains 4-6 % in every kernel with chunks of 64, the single-buffer
+// configuration 2 (67 items in the forward's list) loses 10 % with whole groups or chunks of 64
+// and nothing with chunks of 8-16; the GQA configurations, one group per queue, do not change.
+__device__ __forceinline__ int chunk_items(int n_items) { return min(64, max(8, n_items >> 3)); }
+__device__ __forceinline__ void decode_work(const HeadMap& hm, int n_items, int x, int w, int& item, int& head) {
     if (hm.striped) {
         item = x + kQueues * (w / hm.heads);
         head = w % hm.heads;
     } else {
-        item = w / hm.hpq;
-        const int e = w % hm.hpq;
-        head = (x + kQueues * (e / hm.group)) * hm.group + e % hm.group;
+        const int chunk = chunk_items(n_items);
+        const int per_chunk = chunk * hm.hpq;              // work indices of a full chunk
+        const int ck = w / per_chunk, r = w - ck * per_chunk;
+        const int first = ck * chunk;
+        const int per_group = min(chunk, n_items - first) * hm.group;
+        const int grp = r / per_group, r2 = r - grp * per_group;
+        item = first + r2 / hm.group;
+        head = (x + kQueues * grp) * hm.group + r2 % hm.group;
     }
 }
 
@@ -196,7 +215,7 @@ struct WorkFetcher {
         nxt_head = 0;
         while (tried < kQueues) {
             if (w < queue_size(hm, n_items, q)) {
-                decode_work(hm, q, w, nxt_item, nxt_head);
+                decode_work(hm, n_items, q, w, nxt_item, nxt_head);
                 break;
             }
             if (q == queue) {                       // that queue is exhausted: on to the next one
