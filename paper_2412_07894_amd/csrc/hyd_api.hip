@@ -25,7 +25,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Workspace: one or two schedules (the backward has one per tile size when its two kernels use
 // different tiles), then the backward's row statistics ([Hq][T] floats; the fp32 path uses the
 // first one only) and, for bf16, the fp16 copies of Q, dO and K that its tile loops stream.
-constexpr int kBwdStatVecs = 5;
+constexpr int kBwdStatVecs = 4;
 constexpr int kHdrAbsmax = 40;            // header word of the dK/dV schedule that holds max |dO| (see BwdScratch)
 struct SchedLayout { size_t hdr, lev, order, items; int n_lev, max_items; };
 struct WsLayout {
@@ -399,10 +399,9 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
     if (dt == HYD_BF16) {
         BwdScratch sc;
         sc.Dq = Dvec;
-        sc.lse2q = reinterpret_cast<float*>(ws + w.stat[1]);
-        sc.kqmul = reinterpret_cast<float*>(ws + w.stat[2]);
-        sc.lse2kv = reinterpret_cast<float*>(ws + w.stat[3]);
-        sc.Dkv = reinterpret_cast<float*>(ws + w.stat[4]);
+        sc.kqmul = reinterpret_cast<float*>(ws + w.stat[1]);
+        sc.lse2 = reinterpret_cast<float*>(ws + w.stat[2]);
+        sc.Dkv = reinterpret_cast<float*>(ws + w.stat[3]);
         sc.absmax = reinterpret_cast<uint32_t*>(sv_kv.hdr + kHdrAbsmax);      // the prelude has cleared the header
         sc.q16 = reinterpret_cast<uint16_t*>(ws + w.q16);
         sc.do16 = reinterpret_cast<uint16_t*>(ws + w.do16);

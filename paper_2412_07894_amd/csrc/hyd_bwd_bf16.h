@@ -9,8 +9,9 @@
 // it).  Every bf16 input converts to fp16 exactly as long as its magnitude lies in [2^-14, 65504];
 // dO, whose scale is arbitrary (it is linear in the loss), is brought into that range by powers
 // of two: one per tensor for dK/dV (sums over rows need a common scale), one per row for dQ
-// (folded into the row's -LSE2, so that it costs nothing), both undone when the results are
-// written.  The fp16 copies of Q, K and dO that the tile loops stream are written once per call
+// (applied to the row's dO and D when the dQ kernel takes them into registers), both undone when
+// the results are written.  Powers of two are exact, so the gradients follow a power-of-two scale
+// of dO bit for bit.  The fp16 copies of Q, K and dO that the tile loops stream are written once per call
 // into the workspace.
 //
 // Fragment convention (see hyd_device.h): an MFMA operand fragment is "lane <-> one index, 8
@@ -41,9 +42,8 @@ __device__ __forceinline__ float pow2i(int k) { return __uint_as_float((uint32_t
 // Row statistics and scratch of the backward, all in the caller's workspace.
 struct BwdScratch {
     float* Dq;          // [Hq][T]  -D,  D = rowsum(dO * O)                          (dQ kernel)
-    float* lse2q;       // [Hq][T]  -LSE * log2(e) + kq, kq = shift_of(row max |dO|) (dQ kernel: P * 2^kq)
-    float* kqmul;       // [Hq][T]  2^-kq                                            (dQ kernel's epilogue)
-    float* lse2kv;      // [Hq][T]  -LSE * log2(e)                                   (dK/dV kernel)
+    float* kqmul;       // [Hq][T]  2^-kq, kq = shift_of(row max |dO|)               (dQ kernel: row scale and its inverse)
+    float* lse2;        // [Hq][T]  -LSE * log2(e)                                   (both kernels)
     float* Dkv;         // [Hq][T]  -D * 2^kg, kg = shift_of(max |dO| of the tensor) (dK/dV kernel; written by dQ)
     uint32_t* absmax;   // max over dO of the 15-bit magnitude pattern; zeroed by the schedule prelude
     uint16_t* q16;      // [T][Hq][d]  fp16 copy of Q          (written by the dQ kernel, read by dK/dV)
@@ -118,9 +118,8 @@ __global__ void __launch_bounds__(256) hyd_bwd_rowstats_bf16_kernel(const uint16
             const int64_t at = (int64_t)h * T + t0 + tl;
             const float l2 = -lse[at] * kLog2e, kq = st[(hq + h) * kStatTok + tl];
             sc.Dq[at] = st[idx];
-            sc.lse2q[at] = l2 + kq;
             sc.kqmul[at] = pow2i(-(int)kq);
-            sc.lse2kv[at] = l2;
+            sc.lse2[at] = l2;
         }
     }
     // the tensor's maximum: one atomic per wave at most, and none once the stored value has caught
@@ -152,9 +151,10 @@ struct BwdParams {
 // dS^T then is the B operand of dQ^T[d][q] = K^T dS^T, with K^T fragments from the transposing
 // LDS read of the same K tile.  The K tiles are the fp16 copy (score and dQ products on the fp16
 // MFMA, Q rows from the fp16 copy too); V tiles and dO rows are the caller's bf16 tensors (dP on
-// the bf16 MFMA, exact inputs either way).  The row's P carries the factor 2^kq that brings its dO
-// into fp16's range (it sits in -LSE2), so dS = P (dP - D) is formed for the scaled row and dQ is
-// scaled back by 2^-kq when it is written.
+// the bf16 MFMA, exact inputs either way).  The row's dO and D are multiplied by 2^kq, the power
+// of two that brings the row's largest |dO| into [1, 2), as they are taken into registers, so
+// dS = P (dP - D) is formed for the scaled row (inside fp16's range whatever the scale of the
+// loss) and dQ is scaled back by 2^-kq when it is written.
 // This kernel runs BEFORE dK/dV and, having every Q and dO row of its item in LDS once, also writes
 // what that kernel streams: the fp16 copies of Q and of dO * 2^kg, and -D * 2^kg.
 // ---------------------------------------------------------------------------------------------
@@ -180,7 +180,7 @@ template <int D>
 __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int kb,
                                          const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16], f32x16 (&acc)[D / 32],
                                          float scale_log2, float lse2, float Dq, bool mask, int krel) {
-    // lse2 and Dq hold -LSE2 + kq and -D of the lane's row; qf and the K tile are fp16, dof and the V tile bf16
+    // lse2 and Dq hold -LSE2 and -D * 2^kq of the lane's row; qf and the K tile are fp16, dof (dO * 2^kq) and the V tile bf16
     constexpr int NK = D / 16, NDB = D / 32;
     // instruction order pinned with scheduling fences (see the forward kernel)
     f32x16 s, dp;
@@ -222,7 +222,7 @@ __device__ __forceinline__ void dq_block(int Kt, int Vt, const FragAddr& fa, int
     __builtin_amdgcn_sched_barrier(0);
     auto ds_pair = [&](int j) -> uint32_t {   // scores 2j, 2j+1 of the 16 a lane holds
         const int r = 2 * j;
-        return pack_f16(s[r] * (dp[r] + Dq), s[r + 1] * (dp[r + 1] + Dq));      // s holds P * 2^kq by now
+        return pack_f16(s[r] * (dp[r] + Dq), s[r + 1] * (dp[r + 1] + Dq));      // s holds P by now; dp and Dq carry 2^kq
     };
     u32x4 dcur, dnxt;
 #pragma unroll
@@ -337,11 +337,14 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
         }
         float lse2 = 0.f, Dq = 0.f, unshift = 0.f;
         if (qvalid) {
-            lse2 = p.sc.lse2q[(int64_t)head * p.T + row0 + qrow];
+            lse2 = p.sc.lse2[(int64_t)head * p.T + row0 + qrow];
             Dq = p.sc.Dq[(int64_t)head * p.T + row0 + qrow];
             unshift = p.sc.kqmul[(int64_t)head * p.T + row0 + qrow];
             if (wave_first_half) p.sc.Dkv[(int64_t)head * p.T + row0 + qrow] = Dq * up;
         }
+        // 2^kq, the exact reciprocal of the power of two 2^-kq; rows past the range keep 1
+        const float shift = qvalid ? __uint_as_float((254u << 23) - __float_as_uint(unshift)) : 1.f;
+        Dq *= shift;
         f32x16 acc[D / 32];
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
@@ -404,6 +407,9 @@ __global__ void __launch_bounds__(kDqThreads, 1) hyd_bwd_dq_bf16_kernel(BwdParam
 #pragma unroll
             for (int ks = 0; ks < D / 16; ++ks) {
                 qf[ks] = as_bf16x8(a[ks] ^ sign_flip);
+                // the row's dO times 2^kq (exact: a power of two, and the row's largest element lands in [1, 2))
+#pragma unroll
+                for (int e = 0; e < 4; ++e) b[ks][e] = pack_bf16(bf16_lo(b[ks][e]) * shift, bf16_hi(b[ks][e]) * shift);
                 dof[ks] = as_bf16x8(b[ks]);
             }
         }
@@ -576,7 +582,7 @@ __global__ void __launch_bounds__(kKvThreads, 1) hyd_bwd_dkdv_bf16_kernel(BwdPar
             // waves repeat wave 1's load so that all waves count alike); rows past the sequence
             // read as 0, which is harmless because their Q and dO rows are 0 too
             const int which = wave == 0 ? 0 : 1;
-            const float* src = (which == 0 ? p.sc.lse2kv : p.sc.Dkv) + (int64_t)h * p.T + row0;
+            const float* src = (which == 0 ? p.sc.lse2 : p.sc.Dkv) + (int64_t)h * p.T + row0;
             const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, stat_bytes);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_b*)(smem + stage * kKvStageBytes + 2 * kKvTileBytes + which * kKvBM * 4),
                                                      4, (uint32_t)lane * 4, (uint32_t)qt * kKvBM * 4, 0, 0);

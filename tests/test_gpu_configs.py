@@ -62,7 +62,9 @@ def run_config(cid, n_rows=2000, col_cases=3, n_random_keys=48):
         # key 0 is always in: the cost is that of every row of the sequence for the group's
         # heads whatever the keys are, so more keys are nearly free
         cols = {0, 1, 2, 31, 32, 63, 64, 127, 128, 255, 256, L // 3, L // 2, L - 129, L - 33, L - 2, L - 1}
-        cols |= {int(c) for c in rng.integers(0, L, n_random_keys)}
+        # the longest sequence gets many more: its keys have the longest sums, and every row of the
+        # sequence is evaluated for the group's heads anyway
+        cols |= {int(c) for c in rng.integers(0, L, 1024 if n == 0 else n_random_keys)}
         cols = np.array(sorted(cols & set(range(L))), dtype=np.int32)
         t0 = time.time()
         a, b = orc.cols(q, k, v, do, cu, cfg.scale, s, g, cols)
