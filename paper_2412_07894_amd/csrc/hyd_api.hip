@@ -408,13 +408,14 @@ hyd_status bwd_impl(const void* q, const void* k, const void* v, const void* o, 
         sc.k16 = reinterpret_cast<uint16_t*>(ws + w.k16);
         {
             KernelTimer kt("bwd_rowstats_bf16", st);
-            const dim3 rgrid((unsigned)((total_tokens + kStatTok - 1) / kStatTok));
+            const int stat_tok = rowstats_tokens(hq);
+            const dim3 rgrid((unsigned)((total_tokens + stat_tok - 1) / stat_tok));
             if (head_dim == 64)
                 hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<64>, rgrid, dim3(256), rowstats_lds(hq), st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
+                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv, stat_tok);
             else
                 hipLaunchKernelGGL(hyd_bwd_rowstats_bf16_kernel<kHeadDim>, rgrid, dim3(256), rowstats_lds(hq), st, static_cast<const uint16_t*>(o),
-                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv);
+                                   static_cast<const uint16_t*>(d_o), lse, static_cast<const uint16_t*>(k), sc, total_tokens, hq, hkv, stat_tok);
         }
         BwdParams p;
         p.q = static_cast<const uint16_t*>(q); p.v = static_cast<const uint16_t*>(v); p.d_o = static_cast<const uint16_t*>(d_o);

@@ -52,24 +52,25 @@ struct BwdScratch {
 };
 
 // ---------------------------------------------------------------------------------------------
-// One pass over O, dO and K before the tile kernels (16 lanes per row, 32 tokens per workgroup):
+// One pass over O, dO and K before the tile kernels (16 lanes per row, kStatTok = 32 tokens per workgroup):
 // the row statistics above except Dkv, the tensor's largest |dO|, and the fp16 copy of K.  A
 // workgroup walks the rows of its tokens in memory order and collects their statistics in LDS, so
-// that the [Hq][T] vectors are written in runs of 32 consecutive floats.  The statistics are
+// that the [Hq][T] vectors are written in runs of kStatTok consecutive floats.  The statistics are
 // stored NEGATED: the form in which the two backward kernels consume them
 // (P = exp2(s * scale * log2(e) + (-LSE2)), dS = P * (dP + (-D))), so that dK/dV can use -D as the
 // initial value of its dP accumulator.  (The fp16 copies of Q and dO and Dkv are written by the dQ
 // kernel, which has those rows in LDS anyway.)
 // ---------------------------------------------------------------------------------------------
-constexpr int kStatTok = 32;
-inline size_t rowstats_lds(int hq) { return sizeof(float) * 2 * (size_t)hq * kStatTok; }
+// tokens per workgroup: 32, fewer with very many heads so that the statistics stay within 32 KB of LDS
+inline int rowstats_tokens(int hq) { const int t = 4096 / (hq > 0 ? hq : 1); return t > 32 ? 32 : (t < 1 ? 1 : t); }
+inline size_t rowstats_lds(int hq) { return sizeof(float) * 2 * (size_t)hq * rowstats_tokens(hq); }
 
 template <int HD = kHeadDim>
 __global__ void __launch_bounds__(256) hyd_bwd_rowstats_bf16_kernel(const uint16_t* __restrict__ o,
                                                                    const uint16_t* __restrict__ d_o,
                                                                    const float* __restrict__ lse,
                                                                    const uint16_t* __restrict__ k,
-                                                                   BwdScratch sc, int T, int hq, int hkv) {
+                                                                   BwdScratch sc, int T, int hq, int hkv, int kStatTok) {
     extern __shared__ float st[];                  // [2][hq][kStatTok]: -D, kq
     const int t0 = blockIdx.x * kStatTok;
     const int nt = min(kStatTok, T - t0);

@@ -87,6 +87,11 @@ def test_bf16_head_dim_64_no_cross_contamination():
     assert not np.array_equal(a["o"][:, 2], b["o"][:, 2])
 
 
+def test_bf16_many_heads():
+    # 160 query heads: the statistics pass of the backward takes fewer tokens per workgroup
+    full_parity([70, 33, 130], 160, 40, 64, "bf16", seed=39)
+
+
 def test_bf16_thousands_of_short_sequences():
     # more sequences than the schedule prelude has threads, every item a single partial tile,
     # empty sequences in between
